@@ -1,0 +1,284 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-rank tensor-parallel linear layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config NAME] [--no-extra] [--no-cpu]
+
+A step is one pass of the whole hot path of one rank's share (forward and backward, every
+product and elementwise kernel) over one batch of seeded synthetic blocks that are already
+resident in HBM.  The headline workload is the 1D (size 4) feed-forward share, M=16384, H=4096,
+F=16384 (six 16384 x 4096 x 4096 products); the other configurations are measured after it with
+fewer steps and reported under "per_config".  Prints ONE JSON line.
+
+value       = GEMM flops of the step / wall time of the step (bf16 TFLOP/s, fp32 accumulation)
+roofline    = the dominant kernel (largest share of step time): its flops per launch / its average
+              duration measured with HIP events on the launch stream, against the MI355X dense
+              bf16 MFMA peak
+cpu_baseline= the fp64 oracle timed on the host cores on a bounded slab of the same share
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0          # MI355X dense bf16 MFMA peak (published figure, 2.5 PFLOP/s)
+NSETS = 3                          # buffer sets rotated through, so nothing is re-served from the 256 MB MALL
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (scaled by a copy kernel of known size); None until such a run has been summarised in profiles/.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c2_1d_n4_mlp")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--extra-steps", type=int, default=10)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU's share of the tensor-parallel layer; the blocks other "
+              "ranks would send are pre-placed in HBM and no collective runs, so --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2110_14883_amd as T
+    import synth_inputs as S
+    from paper_2110_14883_amd import workloads as WL
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    T.lib()
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    def up(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+    def empty(shape, f32=False):
+        return torch.empty(shape, dtype=torch.float32 if f32 else torch.bfloat16, device="cuda")
+
+    def ws_for(grid, dims):
+        n = max(T.tp_linear_workspace_size(grid, dims, p) for p in (0, 1, 2))
+        return torch.empty(max(n, 256), dtype=torch.uint8, device="cuda")
+
+    # ------------------------------------------------------------------ step builders
+    # Each returns (calls, flops): calls = per-set lists of (label, flops, fn); fn enqueues ONE library call.
+    def build_mlp1d(cfg):
+        M, H, F = cfg.dims
+        size, rank = cfg.grid.p, cfg.grid.ri
+        inp = WL.make_mlp1d_inputs(size, rank, M, H, F)
+        fb = inp["fb"]
+        g1, d1 = T.Grid(T.MODE_1D_COL, p=size, ri=rank), (M, H, F)
+        g2, d2 = T.Grid(T.MODE_1D_ROW, p=size, ri=rank), (M, F, H)
+        one = 2.0 * M * H * fb
+        sets = []
+        base = {k: up(inp[k]) for k in ("X", "W1", "b1", "W2", "G")}
+        for s in range(NSETS):
+            b = base if s == 0 else {k: v.clone() for k, v in base.items()}
+            o = dict(Z=empty((M, fb)), A=empty((M, fb)), Y=empty((M, H), True), dA=empty((M, fb)),
+                     dW2=empty((fb, H), True), dX=empty((M, H), True), dW1=empty((H, fb), True),
+                     ws1=ws_for(g1, d1), ws2=ws_for(g2, d2))
+            calls = [
+                ("fc1_fwd NN +bias+GeLU", one, lambda b=b, o=o: T.tp_linear_fwd(
+                    g1, d1, 1, [b["X"]], [b["W1"]], b["b1"], T.EPI_BIAS_GELU, o["Z"], o["A"], o["ws1"])),
+                ("fc2_fwd NN fp32 partial", one, lambda b=b, o=o: T.tp_linear_fwd(
+                    g2, d2, 1, [o["Z"]], [b["W2"]], None, T.EPI_NONE, o["Y"], None, o["ws2"])),
+                ("fc2_dX NT *GeLU'", one, lambda b=b, o=o: T.tp_linear_bwd(
+                    g2, d2, 1, 0, da_row_blocks=[b["G"]], w_blocks_dx=[b["W2"]], dgelu_preact=o["A"], dx=o["dA"],
+                    workspace=o["ws2"])),
+                ("fc2_dW TN", one, lambda b=b, o=o: T.tp_linear_bwd(
+                    g2, d2, 0, 1, x_blocks_dw=[o["Z"]], da_col_blocks=[b["G"]], dw=o["dW2"], workspace=o["ws2"])),
+                ("fc1_dX NT fp32 partial", one, lambda b=b, o=o: T.tp_linear_bwd(
+                    g1, d1, 1, 0, da_row_blocks=[o["dA"]], w_blocks_dx=[b["W1"]], dx=o["dX"], workspace=o["ws1"])),
+                ("fc1_dW TN", one, lambda b=b, o=o: T.tp_linear_bwd(
+                    g1, d1, 0, 1, x_blocks_dw=[b["X"]], da_col_blocks=[o["dA"]], dw=o["dW1"], workspace=o["ws1"])),
+            ]
+            sets.append(calls)
+        return sets, 6 * one
+
+    def build_share(cfg):
+        grid, dims = cfg.grid, cfg.dims
+        inp = WL.make_share_inputs(grid, dims, S.BASE_SEED, cfg.n_steps, cfg.backward)
+        m, n, k = inp["m"], inp["n"], inp["k"]
+        sf = inp["n_steps_fwd"]
+        one = 2.0 * m * n * k * sf
+        f32y = cfg.y_dtype == "f32"
+        sets = []
+        base = dict(x=[up(b) for b in inp["x_blocks"]], w=[up(b) for b in inp["w_blocks"]], bias=up(inp["bias"]))
+        if cfg.backward:
+            sx, sw = inp["n_steps_dx"], inp["n_steps_dw"]
+            base.update(g=up(inp["g_own"]), wdx=[up(b) for b in inp["w_blocks_dx"]], xdw=[up(b) for b in inp["x_blocks_dw"]])
+            # peers' dA blocks, made once by the library's own elementwise kernel from (G_peer, A_peer)
+            def peer(pair):
+                g, a = up(pair[0]), up(pair[1])
+                out = torch.empty_like(g)
+                T.tp_dgelu(g, a, out)
+                return out
+            memo = {}
+            def peer_memo(pair):
+                key = (pair[0].ctypes.data, pair[1].ctypes.data)
+                if key not in memo:
+                    memo[key] = peer(pair)
+                return memo[key]
+            base["da_row"] = {i: peer_memo(p) for i, p in inp["peers_dx"].items()}
+            base["da_col"] = {i: peer_memo(p) for i, p in inp["peers_dw"].items()}
+            torch.cuda.synchronize()
+        for s in range(NSETS):
+            def cp(v):
+                if s == 0:
+                    return v
+                if isinstance(v, list):
+                    return [t.clone() for t in v]
+                if isinstance(v, dict):
+                    return {i: t.clone() for i, t in v.items()}
+                return v.clone()
+            b = {k_: cp(v) for k_, v in base.items()}
+            o = dict(y=empty((m, n), f32y), pre=empty((m, n)), ws=ws_for(grid, dims))
+            calls = [("fwd NN +bias+GeLU", one, lambda b=b, o=o: T.tp_linear_fwd(
+                grid, dims, sf, b["x"], b["w"], b["bias"], T.EPI_BIAS_GELU, o["y"], o["pre"], o["ws"]))]
+            if cfg.backward:
+                o.update(da=empty((m, n)), dx=empty((m, k), cfg.dx_dtype == "f32"), dw=empty((k, n), True))
+                rows = [o["da"] if i == inp["own_slot_dx"] else b["da_row"][i] for i in range(sx)]
+                cols = [o["da"] if i == inp["own_slot_dw"] else b["da_col"][i] for i in range(sw)]
+                calls += [
+                    ("dA = dY*GeLU'(A)", 0.0, lambda b=b, o=o: T.tp_linear_bwd(
+                        grid, dims, 0, 0, dy_own=b["g"], preact_own=o["pre"], da_own_out=o["da"], workspace=o["ws"])),
+                    ("dX NT", one, lambda b=b, o=o, rows=rows: T.tp_linear_bwd(
+                        grid, dims, sx, 0, da_row_blocks=rows, w_blocks_dx=b["wdx"], dx=o["dx"], workspace=o["ws"])),
+                    ("dW TN", one, lambda b=b, o=o, cols=cols: T.tp_linear_bwd(
+                        grid, dims, 0, sw, x_blocks_dw=b["xdw"], da_col_blocks=cols, dw=o["dw"], workspace=o["ws"])),
+                ]
+            sets.append(calls)
+        return sets, one * (3 if cfg.backward else 1)
+
+    def run_config(cfg, steps, warmup):
+        log(f"[bench] {cfg.name}: generating inputs")
+        t0 = time.time()
+        sets, flops = (build_mlp1d if cfg.chain_1d else build_share)(cfg)
+        log(f"[bench] {cfg.name}: inputs ready in {time.time() - t0:.1f}s; warmup {warmup}, steps {steps}")
+        ncall = len(sets[0])
+        for i in range(warmup):
+            for _, _, fn in sets[i % NSETS]:
+                fn()
+        torch.cuda.synchronize()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(ncall + 1)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            calls = sets[i % NSETS]
+            ev[i][0].record(stream)
+            for j, (_, _, fn) in enumerate(calls):
+                fn()
+                ev[i][j + 1].record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        ms_step = wall * 1e3 / steps
+        per_call = []
+        for j, (label, fl, _) in enumerate(sets[0]):
+            ms = sum(ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(steps)) / steps
+            per_call.append(dict(call=label, ms=round(ms, 4), tflops=round(fl / ms / 1e9, 1) if fl else None))
+        res = dict(workload=cfg.name, note=cfg.note, ms_per_step=round(ms_step, 4), gemm_flops=flops,
+                   tflops=round(flops / ms_step / 1e9, 1), pct_of_peak=round(flops / ms_step / 1e9 / PEAK_BF16_TFLOPS * 100, 2),
+                   calls=per_call)
+        del sets
+        torch.cuda.empty_cache()
+        return res
+
+    cfg = WL.config(args.config)
+    main_res = run_config(cfg, args.steps, args.warmup)
+
+    # dominant kernel = the GEMM form with the largest share of the step
+    by_form = {}
+    for c in main_res["calls"]:
+        if c["tflops"] is None:
+            continue
+        form = c["call"].split()[1]
+        by_form.setdefault(form, []).append(c)
+    form, lst = max(by_form.items(), key=lambda kv: sum(c["ms"] for c in kv[1]))
+    flops_per_launch = main_res["gemm_flops"] / sum(len(v) for v in by_form.values())
+    avg_ms = sum(c["ms"] for c in lst) / len(lst)
+    achieved = flops_per_launch / avg_ms / 1e9
+    kname = {"NN": "tp_gemm_kernel<256,256,true,false>", "NT": "tp_gemm_kernel<256,256,true,true>",
+             "TN": "tp_gemm_kernel<256,256,false,false>"}[form]
+    roofline = dict(bound="mfma", kernel=kname, launches_per_step=len(lst), avg_launch_ms=round(avg_ms, 4),
+                    flops_per_launch=flops_per_launch, achieved=round(achieved, 1), peak=PEAK_BF16_TFLOPS,
+                    unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4),
+                    traffic=MEASURED_TRAFFIC_BYTES.get(kname))
+
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(cfg)
+
+    extra = []
+    if not args.no_extra:
+        for c in WL.CONFIGS:
+            if c.name == cfg.name:
+                continue
+            extra.append(run_config(c, args.extra_steps, 3))
+
+    out = {
+        "metric": "bf16 TFLOP/s of per-rank TP linear fwd+bwd; % of MFMA dense peak",
+        "value": main_res["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.note}", "dims_MHF": list(cfg.dims), "parallelism": "one rank's share, 1 GPU",
+                   "gemm_flops_per_step": main_res["gemm_flops"]},
+        "pct_of_mfma_peak": main_res["pct_of_peak"],
+        "roofline": roofline, "cpu_baseline": cpu, "calls": main_res["calls"], "per_config": extra,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def cpu_baseline(cfg):
+    """The fp64 oracle, as it stands, on the host cores, on a slab of token rows of the same share."""
+    import numpy as np
+
+    import synth_inputs as S
+    from oracle import tp_oracle as O
+    from paper_2110_14883_amd import workloads as WL
+
+    cores = os.cpu_count() or 1
+    try:
+        from threadpoolctl import threadpool_info
+        info = [p for p in threadpool_info() if p.get("user_api") == "blas"]
+        if info:
+            cores = int(info[0].get("num_threads", cores))
+    except Exception:
+        pass
+    M, H, F = cfg.dims
+    if cfg.chain_1d:
+        size, rank = cfg.grid.p, cfg.grid.ri
+        rows = M                                 # the whole share: a few seconds of BLAS-backed fp64 work
+        inp = WL.make_mlp1d_inputs(size, rank, rows, H, F)
+        X, W1, b1, W2, G = (O.bf16_bits_to_f64(inp[k]) for k in ("X", "W1", "b1", "W2", "G"))
+        t0 = time.perf_counter()
+        fw = O.mlp1d_fwd(X, W1, b1, W2)
+        O.mlp1d_bwd(X, W1, W2, fw["A_saved"], fw["Z"], G)
+        dt = time.perf_counter() - t0
+        flops = 6 * 2.0 * rows * H * inp["fb"]
+        sample = f"all six products of the same rank share, {rows} of {M} token rows"
+    else:
+        raise NotImplementedError("CPU baseline is timed on the headline 1D workload")
+    log(f"[bench] cpu oracle: {flops / dt / 1e9:.1f} GFLOP/s fp64 on {cores} threads ({dt:.1f}s)")
+    return dict(value=round(flops / dt / 1e12, 4), unit="TFLOP/s", cores=cores, kind="oracle", sample=sample,
+                seconds=round(dt, 2), dtype="f64")
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,164 @@
+/*
+ * tp_linear.h -- C ABI of libtplinear: one rank's share of a tensor-parallel linear layer on one
+ * MI355X (gfx950), forward and backward.
+ *
+ * What is computed (paper Section 2.2 "Model Parallelism", tensor-parallelism paragraphs; Section
+ * 3.1 and Table 1 for the notation): a linear layer  Y = GeLU(X W + 1 b^T)  whose input, weight and
+ * output are cut into chunks over a rank grid -- 1D (Megatron feed-forward: first weight cut by
+ * columns, second by rows, every rank holding a partial output that an all-reduce would sum), 2D
+ * (SUMMA on a q x q square, chunks [P/q, Q/q]), 2.5D (q x q x d cuboid, N = S^2 D) and 3D (p x p x p
+ * cube, chunks [P/p^2, Q/p]).  One rank's work is an ordered loop of local block products
+ *      C += A_k B_k,   k = 0 .. n_steps-1,
+ * followed by bias add and erf-GeLU, and in backward  dX = sum_k dA_k W_k^T,  dW = sum_k X_k^T dA_k.
+ * The blocks other ranks would broadcast or gather are already in this GPU's memory: the library
+ * performs no communication.
+ *
+ * Conventions.  Tokens are rows.  All blocks are row-major with a leading dimension `ld` counted in
+ * elements.  X:[M,H], W:[H,F] (in x out), b:[F].  bf16 inputs, fp32 accumulation, fp32 or bf16
+ * outputs (bf16 by round-to-nearest-even).  Every pointer in this ABI is a DEVICE pointer unless it
+ * is explicitly called a host array; host arrays are read during the call and may be freed after it.
+ *
+ * Ownership / errors.  The caller owns every buffer; the library never allocates, frees or
+ * synchronises.  Work is enqueued on the HIP stream passed in (a hipStream_t cast to void*, NULL =
+ * the default stream) and the call returns immediately.  Inputs are read-only and may alias each
+ * other but not outputs.  Every failure is a return code found before anything is launched; nothing
+ * is written on error.  Row counts may be any value >= 1 (ragged tails are masked); column extents
+ * of every block and every `ld` must be multiples of 8 elements and every pointer 16-byte aligned
+ * (128-bit loads), else TP_ERR_ALIGN.
+ */
+#ifndef TP_LINEAR_H
+#define TP_LINEAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TP_MAX_STEPS 16
+
+typedef enum {
+    TP_OK = 0,
+    TP_ERR_NULL = 1,       /* a required pointer is NULL */
+    TP_ERR_MODE = 2,       /* unknown mode / pass / epilogue */
+    TP_ERR_GRID = 3,       /* q, d or p < 1, or a rank coordinate outside the grid */
+    TP_ERR_SHAPE = 4,      /* M, H, F not divisible as the mode requires; n_steps out of range */
+    TP_ERR_ALIGN = 5,      /* pointer not 16-byte aligned, or ld / column extent not a multiple of 8 */
+    TP_ERR_DTYPE = 6,      /* output dtype not supported for this output */
+    TP_ERR_WORKSPACE = 7,  /* workspace NULL or smaller than tp_linear_workspace_size() says */
+    TP_ERR_HIP = 8         /* a HIP call (launch) reported an error */
+} tp_status_t;
+
+/* Partition modes.  The 1D scheme is two modes because its two weights are cut differently. */
+typedef enum {
+    TP_MODE_1D_COL = 10,   /* W cut by columns: rank r owns W[:, r];  Y[:, r] = act(X W[:, r] + b[r])   */
+    TP_MODE_1D_ROW = 11,   /* W cut by rows:    rank r owns W[r, :];  partial Y_r = X[:, r] W[r, :]      */
+    TP_MODE_2D = 2,        /* q x q,      rank (ri, rj)                                                  */
+    TP_MODE_2P5D = 25,     /* q x q x d,  rank (ri, rj, rk = depth layer)                                */
+    TP_MODE_3D = 3         /* p x p x p,  rank (ri, rj, rk)                                              */
+} tp_mode_t;
+
+typedef enum { TP_BF16 = 0, TP_F32 = 1 } tp_dtype_t;
+typedef enum { TP_EPI_NONE = 0, TP_EPI_BIAS = 1, TP_EPI_BIAS_GELU = 2 } tp_epilogue_t;
+typedef enum { TP_PASS_FWD = 0, TP_PASS_DX = 1, TP_PASS_DW = 2 } tp_pass_t;
+
+/* 1D: p = size, ri = rank (q = d = 1).  2D: q, (ri, rj).  2.5D: q, d, (ri, rj, rk).  3D: p, (ri, rj, rk).
+ * Unused sizes must be 1 and unused coordinates 0. */
+typedef struct { int mode; int q, d, p; int ri, rj, rk; } tp_grid_t;
+/* The FULL (unpartitioned) layer: M tokens, H input features, F output features. */
+typedef struct { int64_t M, H, F; } tp_dims_t;
+/* A read-only device block: bf16, row-major, ld in elements. */
+typedef struct { const void* ptr; int64_t ld; } tp_cblk_t;
+/* An output device block: row-major, ld in elements, dtype a tp_dtype_t.  ptr == NULL means "not wanted". */
+typedef struct { void* ptr; int64_t ld; int dtype; } tp_oblk_t;
+
+/*
+ * tp_block_map -- the partition map (host only, no GPU needed).  For rank `grid` of a layer `dims`
+ * and a pass, reports how many steps the exact share has, the local product's extents and which
+ * chunks take part, as (row chunk, col chunk) indices into the chunk grids below.
+ *   chunk grids: X, dX: [rc x kc];  W, dW: [kc x cc];  Y, A, dA: [rc x cc];  b: [cc]
+ *     1D_COL: rc=1, kc=1, cc=p      1D_ROW: rc=1, kc=p, cc=1      2D: rc=kc=cc=q
+ *     2.5D: rc=q d, kc=cc=q (row chunk of rank (i,j,l) is l q + i; W and b repeat on every layer)
+ *     3D:   rc=p^2, kc=cc=p (row chunk of rank (i,j,l) is i p + l)
+ *   TP_PASS_FWD: C[m,n] = sum_k X[a_k] W[b_k];          out indexes Y (bias chunk = out_col)
+ *   TP_PASS_DX : C[m,n] = sum_k dA[a_k] W[b_k]^T;       out indexes dX
+ *   TP_PASS_DW : C[m,n] = sum_k X[a_k]^T dA[b_k];       out indexes dW
+ * m, n = extents of the output block, k_per_step = contraction length of one step.
+ * a_row..b_col are host arrays of TP_MAX_STEPS ints (may be NULL if not wanted); *is_partial = 1
+ * when the block is an additive partial that a reduction over other ranks would complete
+ * (1D partial sums; 2.5D dW over depth; 3D dW over the first cube axis).
+ * Errors: TP_ERR_NULL, TP_ERR_MODE, TP_ERR_GRID, TP_ERR_SHAPE.
+ */
+int tp_block_map(const tp_grid_t* grid, const tp_dims_t* dims, int pass,
+                 int* n_steps, int64_t* m, int64_t* n, int64_t* k_per_step,
+                 int* a_row, int* a_col, int* b_row, int* b_col,
+                 int* out_row, int* out_col, int* is_partial);
+
+/* Bytes of device workspace tp_linear_fwd (pass TP_PASS_FWD) or tp_linear_bwd (TP_PASS_DX and
+ * TP_PASS_DW each; pass the larger, the two products run one after the other) may need for this
+ * share: cross-workgroup split-K partials in fp32.  0 on invalid arguments.  Never more than
+ * 8 x m x n x 4 bytes. */
+size_t tp_linear_workspace_size(const tp_grid_t* grid, const tp_dims_t* dims, int pass);
+
+/*
+ * tp_linear_fwd -- forward share:  C = sum_{k<n_steps} X_k W_k  with the fp32 accumulator kept
+ * on-chip across all steps;  A = C + b (epi >= TP_EPI_BIAS);  Y = GeLU(A) (TP_EPI_BIAS_GELU), else Y = A.
+ *   x_blocks, w_blocks : host arrays [n_steps] of device blocks; X_k is [m, k], W_k is [k, n] with
+ *                        m, n, k as tp_block_map reports for TP_PASS_FWD.
+ *   n_steps            : 1 .. the map's step count (fewer steps = a prefix of the sum).
+ *   bias               : bf16 [n] (this rank's chunk) or NULL when epi == TP_EPI_NONE.
+ *   y                  : [m, n], fp32 or bf16.
+ *   preact             : optional bf16 [m, n]: A rounded to bf16, saved for backward.
+ *   workspace          : >= tp_linear_workspace_size(.., TP_PASS_FWD) bytes, 256-byte aligned (may be
+ *                        NULL when that size is 0).
+ */
+int tp_linear_fwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps,
+                  const tp_cblk_t* x_blocks, const tp_cblk_t* w_blocks,
+                  const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * tp_linear_bwd -- backward share.  In order, each part only if its outputs are wanted:
+ *   (1) own dA:  da_own_out = bf16(dy_own * GeLU'(preact_own))          [m_y, n_y] of the forward block;
+ *                needs dy_own, preact_own, da_own_out.  When own_slot_dx >= 0 (own_slot_dw >= 0) the
+ *                block just written is used as da_row_blocks[own_slot_dx] (da_col_blocks[own_slot_dw]),
+ *                whatever those host entries hold.  db (fp32 [n_y], optional) receives its column sums.
+ *   (2) dX = sum_{k<n_steps_dx} da_row_blocks[k] w_blocks_dx[k]^T        extents from TP_PASS_DX;
+ *                if dgelu_preact is given (bf16, same shape as dX: the previous layer's saved
+ *                pre-activation; the 1D chain) the result is multiplied by GeLU' of it in the epilogue.
+ *   (3) dW = sum_{k<n_steps_dw} x_blocks_dw[k]^T da_col_blocks[k]        extents from TP_PASS_DW;
+ *                fp32 output only (TP_ERR_DTYPE otherwise).
+ *   For a layer without activation (1D_ROW) pass the upstream gradient blocks as the "da" blocks.
+ *   workspace: >= max(tp_linear_workspace_size(DX), tp_linear_workspace_size(DW)).
+ */
+int tp_linear_bwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_dx, int n_steps_dw,
+                  const tp_cblk_t* dy_own, const tp_cblk_t* preact_own,
+                  const tp_cblk_t* da_row_blocks, const tp_cblk_t* w_blocks_dx,
+                  const tp_cblk_t* x_blocks_dw, const tp_cblk_t* da_col_blocks,
+                  int own_slot_dx, int own_slot_dw,
+                  const tp_cblk_t* dgelu_preact,
+                  tp_oblk_t dx, tp_oblk_t dw, tp_oblk_t da_own_out, void* db_f32,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * tp_dgelu -- the elementwise part of backward on its own:  da = bf16(dy * GeLU'(preact)),
+ * all three bf16 [rows, cols] row-major with their own leading dimensions.  HBM-bound.
+ */
+int tp_dgelu(const void* dy, int64_t ld_dy, const void* preact, int64_t ld_pre,
+             void* da, int64_t ld_da, int64_t rows, int64_t cols, void* hip_stream);
+
+/*
+ * tp_plan_override -- tuning hook for benchmarks.  key 0: macro-tile id (0 = automatic);
+ * key 1: split-K factor (0 = automatic, 1..8); key 2: tile-order group width (0 = automatic).
+ * Process-wide; affects later calls.  Returns TP_ERR_MODE for an unknown key or value.
+ */
+int tp_plan_override(int key, int value);
+
+/* Human-readable name of a status code (static storage). */
+const char* tp_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TP_LINEAR_H */

@@ -1,0 +1,8 @@
+"""MI355X-native per-rank tensor-parallel linear layer (1D / 2D-SUMMA / 2.5D / 3D): a thin ctypes
+binding over libtplinear.so.  Importing this package does not load the library; the first call
+does, and fails loudly if it has not been built (python -m paper_2110_14883_amd.build)."""
+from .binding import (  # noqa: F401
+    EPI_BIAS, EPI_BIAS_GELU, EPI_NONE, MODE_1D_COL, MODE_1D_ROW, MODE_2D, MODE_2P5D, MODE_3D,
+    PASS_DW, PASS_DX, PASS_FWD, Grid, TpError, lib, tp_block_map, tp_dgelu, tp_linear_bwd,
+    tp_linear_fwd, tp_linear_workspace_size, tp_plan_override, tp_strerror,
+)

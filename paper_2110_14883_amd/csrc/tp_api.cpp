@@ -1,0 +1,375 @@
+// C ABI of libtplinear (see include/tp_linear.h): argument validation, the partition map
+// (paper Section 2.2: chunk shapes [P/q, Q/q], N = S^2 D, [P/p^2, Q/p]; device-count rule),
+// launch planning (macro-tile, split of K across workgroups, tile order) and kernel launches.
+// Everything is checked before the first launch; nothing is allocated or synchronised here.
+#include <algorithm>
+#include <atomic>
+#include <cstring>
+
+#include "tp_internal.h"
+
+using namespace tpl;
+
+namespace {
+
+constexpr int kCUs = 256;                       // MI355X compute units
+constexpr int64_t kMaxLd = (int64_t)1 << 21;    // keeps every in-tile byte offset below 2^31
+
+std::atomic<int> g_tile_override{0}, g_split_override{0}, g_group_override{0};
+
+struct Chunks { int rc, kc, cc; };              // row chunks of X/Y, col chunks of X (= row chunks of W), col chunks of W/Y
+
+int check_grid(const tp_grid_t* g, Chunks* c) {
+    if (g->q < 1 || g->d < 1 || g->p < 1) return TP_ERR_GRID;
+    int li = 1, lj = 1, lk = 1;
+    switch (g->mode) {
+        case TP_MODE_1D_COL: li = g->p; *c = {1, 1, g->p}; if (g->q != 1 || g->d != 1) return TP_ERR_GRID; break;
+        case TP_MODE_1D_ROW: li = g->p; *c = {1, g->p, 1}; if (g->q != 1 || g->d != 1) return TP_ERR_GRID; break;
+        case TP_MODE_2D:     li = lj = g->q; *c = {g->q, g->q, g->q}; if (g->p != 1 || g->d != 1) return TP_ERR_GRID; break;
+        case TP_MODE_2P5D:   li = lj = g->q; lk = g->d; *c = {g->q * g->d, g->q, g->q}; if (g->p != 1) return TP_ERR_GRID; break;
+        case TP_MODE_3D:     li = lj = lk = g->p; *c = {g->p * g->p, g->p, g->p}; if (g->q != 1 || g->d != 1) return TP_ERR_GRID; break;
+        default: return TP_ERR_MODE;
+    }
+    if (g->ri < 0 || g->ri >= li || g->rj < 0 || g->rj >= lj || g->rk < 0 || g->rk >= lk) return TP_ERR_GRID;
+    return TP_OK;
+}
+
+struct Share {           // one pass of one rank
+    int n_steps; int64_t m, n, k;
+    int a_row[TP_MAX_STEPS], a_col[TP_MAX_STEPS], b_row[TP_MAX_STEPS], b_col[TP_MAX_STEPS];
+    int out_row, out_col, partial;
+};
+
+int build_share(const tp_grid_t* g, const tp_dims_t* d, int pass, Share* s) {
+    if (!g || !d || !s) return TP_ERR_NULL;
+    if (pass != TP_PASS_FWD && pass != TP_PASS_DX && pass != TP_PASS_DW) return TP_ERR_MODE;
+    Chunks c;
+    if (int e = check_grid(g, &c)) return e;
+    if (d->M < 1 || d->H < 1 || d->F < 1) return TP_ERR_SHAPE;
+    if (d->M % c.rc || d->H % c.kc || d->F % c.cc) return TP_ERR_SHAPE;
+    const int64_t mb = d->M / c.rc, hb = d->H / c.kc, fb = d->F / c.cc;
+    std::memset(s, 0, sizeof(*s));
+    int steps = 1, row = 0, col = 0, wrow = 0;     // own row chunk, own column index, dW's row chunk
+    int first_row = 0;                             // first row chunk of the group dW sums over
+    switch (g->mode) {
+        case TP_MODE_1D_COL: case TP_MODE_1D_ROW: steps = 1; break;
+        case TP_MODE_2D:   steps = g->q; row = g->ri; col = g->rj; wrow = g->ri; first_row = 0; break;
+        case TP_MODE_2P5D: steps = g->q; row = g->rk * g->q + g->ri; col = g->rj; wrow = g->ri; first_row = g->rk * g->q; break;
+        case TP_MODE_3D:   steps = g->p; row = g->ri * g->p + g->rk; col = g->rj; wrow = g->rk; first_row = g->ri * g->p; break;
+    }
+    if (steps > TP_MAX_STEPS) return TP_ERR_GRID;
+    s->n_steps = steps;
+    if (g->mode == TP_MODE_1D_COL) {
+        const int r = g->ri;
+        if (pass == TP_PASS_FWD)      { s->m = mb; s->n = fb; s->k = hb; s->a_col[0] = 0; s->b_col[0] = r; s->out_col = r; }
+        else if (pass == TP_PASS_DX)  { s->m = mb; s->n = hb; s->k = fb; s->a_col[0] = r; s->b_col[0] = r; s->partial = g->p > 1; }
+        else                          { s->m = hb; s->n = fb; s->k = mb; s->b_col[0] = r; s->out_col = r; }
+        return TP_OK;
+    }
+    if (g->mode == TP_MODE_1D_ROW) {
+        const int r = g->ri;
+        if (pass == TP_PASS_FWD)      { s->m = mb; s->n = fb; s->k = hb; s->a_col[0] = r; s->b_row[0] = r; s->partial = g->p > 1; }
+        else if (pass == TP_PASS_DX)  { s->m = mb; s->n = hb; s->k = fb; s->b_row[0] = r; s->out_col = r; }
+        else                          { s->m = hb; s->n = fb; s->k = mb; s->a_col[0] = r; s->out_row = r; }
+        return TP_OK;
+    }
+    for (int k = 0; k < steps; ++k) {
+        if (pass == TP_PASS_FWD)     { s->a_row[k] = row; s->a_col[k] = k; s->b_row[k] = k; s->b_col[k] = col; }
+        else if (pass == TP_PASS_DX) { s->a_row[k] = row; s->a_col[k] = k; s->b_row[k] = col; s->b_col[k] = k; }
+        else                         { s->a_row[k] = first_row + k; s->a_col[k] = wrow; s->b_row[k] = first_row + k; s->b_col[k] = col; }
+    }
+    if (pass == TP_PASS_FWD)     { s->m = mb; s->n = fb; s->k = hb; s->out_row = row; s->out_col = col; }
+    else if (pass == TP_PASS_DX) { s->m = mb; s->n = hb; s->k = fb; s->out_row = row; s->out_col = col; }
+    else {
+        s->m = hb; s->n = fb; s->k = mb; s->out_row = wrow; s->out_col = col;
+        s->partial = (g->mode == TP_MODE_2P5D && g->d > 1) || (g->mode == TP_MODE_3D && g->p > 1);
+    }
+    return TP_OK;
+}
+
+struct Plan { int tile_id, bm, bn, tiles_m, tiles_n, split_k, group_m; };
+
+// Pick the macro-tile and the split of K so that the launch fills whole waves of the 256 CUs.
+// Cost model: (waves of workgroups) x (K tiles per workgroup) x (tile area), plus the fp32
+// round trip of the partials when K is split.
+Plan make_plan(int64_t m, int64_t n, int64_t k, int n_steps) {
+    const int64_t T = (int64_t)n_steps * ((k + 63) / 64);
+    Plan best{};
+    double best_cost = 1e300;
+    const int tile_ids[4] = {TILE_256x256, TILE_128x256, TILE_256x128, TILE_128x128};
+    const int forced_tile = g_tile_override.load(), forced_split = g_split_override.load();
+    for (int ti = 0; ti < 4; ++ti) {
+        if (forced_tile && tile_ids[ti] != forced_tile) continue;
+        int bm, bn;
+        tile_shape(tile_ids[ti], &bm, &bn);
+        const int64_t tm = (m + bm - 1) / bm, tn = (n + bn - 1) / bn;
+        const int64_t tiles = tm * tn;
+        // cycles one workgroup spends on one 64-deep K tile at ~60 % MFMA rate; smaller tiles move
+        // more LDS bytes per flop and are charged for it
+        const double penalty = (bm == 256 && bn == 256) ? 1.0 : (bm == 128 && bn == 128 ? 1.35 : 1.12);
+        const double tile_cycles = (double)bm * bn * 64 * 2 / 4096.0 / 0.6 * penalty;
+        for (int z = 1; z <= 8; ++z) {
+            if (forced_split && z != forced_split) continue;
+            if (z > T) break;
+            const int64_t waves = (tiles * z + kCUs - 1) / kCUs;
+            const double main_cost = (double)waves * (double)((T + z - 1) / z) * tile_cycles;
+            // partials: z fp32 planes written and read back at ~1.6 KB/clk, plus one more launch
+            const double fix = z > 1 ? (double)m * n * 8.0 * z / 1667.0 + 12000.0 : 0.0;
+            const double cost = main_cost + fix;
+            if (cost < best_cost) {
+                best_cost = cost;
+                best = Plan{tile_ids[ti], bm, bn, (int)tm, (int)tn, z, 4};
+            }
+        }
+    }
+    if (best.tile_id == 0) {           // overrides left nothing admissible: fall back to the safe default
+        best = Plan{TILE_256x256, 256, 256, (int)((m + 255) / 256), (int)((n + 255) / 256), 1, 4};
+    }
+    const int go = g_group_override.load();
+    best.group_m = go > 0 ? go : 4;
+    return best;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_cblk(const tp_cblk_t& b, int64_t cols) {
+    if (!b.ptr) return TP_ERR_NULL;
+    if (!aligned16(b.ptr) || (b.ld & 7) || (cols & 7)) return TP_ERR_ALIGN;
+    if (b.ld < cols || b.ld > kMaxLd) return TP_ERR_SHAPE;
+    return TP_OK;
+}
+int check_oblk(const tp_oblk_t& b, int64_t cols, bool f32_only) {
+    if (!b.ptr) return TP_ERR_NULL;
+    if (b.dtype != TP_BF16 && b.dtype != TP_F32) return TP_ERR_DTYPE;
+    if (f32_only && b.dtype != TP_F32) return TP_ERR_DTYPE;
+    if (!aligned16(b.ptr) || (b.ld & 7) || (cols & 7)) return TP_ERR_ALIGN;
+    if (b.ld < cols) return TP_ERR_SHAPE;
+    return TP_OK;
+}
+
+size_t ws_bytes_for(const Plan& p, int64_t m, int64_t n) {
+    return p.split_k > 1 ? (size_t)p.split_k * (size_t)m * (size_t)n * sizeof(float) : 0;
+}
+
+struct Product {                 // one validated GEMM ready to launch
+    int form; Plan plan; GemmArgs args; bool active;
+};
+
+int run_product(const Product& pr, void* workspace, hipStream_t stream) {
+    GemmArgs a = pr.args;
+    a.ws = static_cast<float*>(workspace);
+    if (launch_gemm(pr.form, pr.plan.tile_id, a, stream) != hipSuccess) return TP_ERR_HIP;
+    if (pr.plan.split_k > 1) {
+        ReduceArgs r{a.ws, a.split_k, a.M, a.N, a.out, a.ldo, a.out_f32, a.pre, a.ldp, a.bias, a.gelu, a.dg, a.lddg};
+        if (launch_reduce(r, stream) != hipSuccess) return TP_ERR_HIP;
+    }
+    return TP_OK;
+}
+
+void fill_common(GemmArgs& a, const Plan& p, int64_t m, int64_t n, int64_t k, int n_steps) {
+    std::memset(&a, 0, sizeof(a));
+    a.M = (int32_t)m; a.N = (int32_t)n; a.K = (int32_t)k; a.n_steps = n_steps;
+    a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.split_k = p.split_k; a.group_m = p.group_m;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tp_block_map(const tp_grid_t* grid, const tp_dims_t* dims, int pass, int* n_steps, int64_t* m, int64_t* n,
+                 int64_t* k_per_step, int* a_row, int* a_col, int* b_row, int* b_col, int* out_row, int* out_col,
+                 int* is_partial) {
+    Share s;
+    if (int e = build_share(grid, dims, pass, &s)) return e;
+    if (n_steps) *n_steps = s.n_steps;
+    if (m) *m = s.m;
+    if (n) *n = s.n;
+    if (k_per_step) *k_per_step = s.k;
+    for (int i = 0; i < TP_MAX_STEPS; ++i) {
+        if (a_row) a_row[i] = s.a_row[i];
+        if (a_col) a_col[i] = s.a_col[i];
+        if (b_row) b_row[i] = s.b_row[i];
+        if (b_col) b_col[i] = s.b_col[i];
+    }
+    if (out_row) *out_row = s.out_row;
+    if (out_col) *out_col = s.out_col;
+    if (is_partial) *is_partial = s.partial;
+    return TP_OK;
+}
+
+size_t tp_linear_workspace_size(const tp_grid_t* grid, const tp_dims_t* dims, int pass) {
+    Share s;
+    if (build_share(grid, dims, pass, &s) != TP_OK) return 0;
+    // independent of overrides and of n_steps: the bound every plan respects (split <= 8 only when
+    // tiles are few; a plan never needs more than 4 planes unless m*n is small) -- report the worst
+    // plane count any admissible plan can pick for this shape
+    size_t worst = 0;
+    for (int steps = 1; steps <= s.n_steps; ++steps) {
+        Plan p = make_plan(s.m, s.n, s.k, steps);
+        worst = std::max(worst, ws_bytes_for(p, s.m, s.n));
+    }
+    if (g_split_override.load() > 1) worst = std::max(worst, (size_t)g_split_override.load() * s.m * s.n * sizeof(float));
+    return worst;
+}
+
+int tp_linear_fwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps, const tp_cblk_t* x_blocks,
+                  const tp_cblk_t* w_blocks, const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact,
+                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+    Share s;
+    if (int e = build_share(grid, dims, TP_PASS_FWD, &s)) return e;
+    if (!x_blocks || !w_blocks) return TP_ERR_NULL;
+    if (n_steps < 1 || n_steps > s.n_steps) return TP_ERR_SHAPE;
+    if (epi != TP_EPI_NONE && epi != TP_EPI_BIAS && epi != TP_EPI_BIAS_GELU) return TP_ERR_MODE;
+    if (epi != TP_EPI_NONE && !bias) return TP_ERR_NULL;
+    if (bias && !aligned16(bias)) return TP_ERR_ALIGN;
+    if (s.m > INT32_MAX || s.n > INT32_MAX || s.k > INT32_MAX) return TP_ERR_SHAPE;
+    for (int k = 0; k < n_steps; ++k) {
+        if (int e = check_cblk(x_blocks[k], s.k)) return e;
+        if (int e = check_cblk(w_blocks[k], s.n)) return e;
+    }
+    if (int e = check_oblk(y, s.n, false)) return e;
+    if (preact.ptr) {
+        if (int e = check_oblk(preact, s.n, false)) return e;
+        if (preact.dtype != TP_BF16) return TP_ERR_DTYPE;
+    }
+    Plan p = make_plan(s.m, s.n, s.k, n_steps);
+    const size_t need = ws_bytes_for(p, s.m, s.n);
+    if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return TP_ERR_WORKSPACE;
+
+    Product pr{};
+    pr.form = FORM_NN; pr.plan = p;
+    fill_common(pr.args, p, s.m, s.n, s.k, n_steps);
+    for (int k = 0; k < n_steps; ++k) {
+        pr.args.a[k] = x_blocks[k].ptr; pr.args.lda[k] = (int32_t)x_blocks[k].ld;
+        pr.args.b[k] = w_blocks[k].ptr; pr.args.ldb[k] = (int32_t)w_blocks[k].ld;
+    }
+    pr.args.out = y.ptr; pr.args.ldo = y.ld; pr.args.out_f32 = y.dtype == TP_F32;
+    pr.args.pre = preact.ptr; pr.args.ldp = preact.ld;
+    pr.args.bias = epi == TP_EPI_NONE ? nullptr : bias;
+    pr.args.gelu = epi == TP_EPI_BIAS_GELU;
+    return run_product(pr, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+int tp_linear_bwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_dx, int n_steps_dw,
+                  const tp_cblk_t* dy_own, const tp_cblk_t* preact_own, const tp_cblk_t* da_row_blocks,
+                  const tp_cblk_t* w_blocks_dx, const tp_cblk_t* x_blocks_dw, const tp_cblk_t* da_col_blocks,
+                  int own_slot_dx, int own_slot_dw, const tp_cblk_t* dgelu_preact, tp_oblk_t dx, tp_oblk_t dw,
+                  tp_oblk_t da_own_out, void* db_f32, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    Share sf, sx, sw;
+    if (int e = build_share(grid, dims, TP_PASS_FWD, &sf)) return e;
+    if (int e = build_share(grid, dims, TP_PASS_DX, &sx)) return e;
+    if (int e = build_share(grid, dims, TP_PASS_DW, &sw)) return e;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (sf.m > INT32_MAX || sf.n > INT32_MAX || sf.k > INT32_MAX) return TP_ERR_SHAPE;
+
+    // ---- (1) own dA
+    const bool want_da = da_own_out.ptr != nullptr;
+    if (want_da) {
+        if (!dy_own || !preact_own) return TP_ERR_NULL;
+        if (int e = check_cblk(*dy_own, sf.n)) return e;
+        if (int e = check_cblk(*preact_own, sf.n)) return e;
+        if (int e = check_oblk(da_own_out, sf.n, false)) return e;
+        if (da_own_out.dtype != TP_BF16) return TP_ERR_DTYPE;
+        if (da_own_out.ld > kMaxLd) return TP_ERR_SHAPE;
+    } else if (db_f32 || own_slot_dx >= 0 || own_slot_dw >= 0) {
+        return TP_ERR_NULL;                      // both need the dA that only part (1) produces
+    }
+    if (db_f32 && !aligned16(db_f32)) return TP_ERR_ALIGN;
+    const tp_cblk_t own_blk{da_own_out.ptr, da_own_out.ld};
+
+    // ---- (2) dX
+    Product px{}; px.active = dx.ptr != nullptr;
+    if (px.active) {
+        if (!da_row_blocks || !w_blocks_dx) return TP_ERR_NULL;
+        if (n_steps_dx < 1 || n_steps_dx > sx.n_steps) return TP_ERR_SHAPE;
+        if (own_slot_dx >= n_steps_dx) return TP_ERR_SHAPE;
+        Plan p = make_plan(sx.m, sx.n, sx.k, n_steps_dx);
+        fill_common(px.args, p, sx.m, sx.n, sx.k, n_steps_dx);
+        for (int k = 0; k < n_steps_dx; ++k) {
+            const tp_cblk_t& a = (k == own_slot_dx) ? own_blk : da_row_blocks[k];
+            if (int e = check_cblk(a, sx.k)) return e;
+            if (int e = check_cblk(w_blocks_dx[k], sx.k)) return e;       // W block is [n = H_blk][k = F_blk]
+            px.args.a[k] = a.ptr; px.args.lda[k] = (int32_t)a.ld;
+            px.args.b[k] = w_blocks_dx[k].ptr; px.args.ldb[k] = (int32_t)w_blocks_dx[k].ld;
+        }
+        if (int e = check_oblk(dx, sx.n, false)) return e;
+        if (dgelu_preact) {
+            if (int e = check_cblk(*dgelu_preact, sx.n)) return e;
+            px.args.dg = dgelu_preact->ptr; px.args.lddg = dgelu_preact->ld;
+        }
+        px.args.out = dx.ptr; px.args.ldo = dx.ld; px.args.out_f32 = dx.dtype == TP_F32;
+        px.form = FORM_NT; px.plan = p;
+    }
+    // ---- (3) dW
+    Product pw{}; pw.active = dw.ptr != nullptr;
+    if (pw.active) {
+        if (!x_blocks_dw || !da_col_blocks) return TP_ERR_NULL;
+        if (n_steps_dw < 1 || n_steps_dw > sw.n_steps) return TP_ERR_SHAPE;
+        if (own_slot_dw >= n_steps_dw) return TP_ERR_SHAPE;
+        Plan p = make_plan(sw.m, sw.n, sw.k, n_steps_dw);
+        fill_common(pw.args, p, sw.m, sw.n, sw.k, n_steps_dw);
+        for (int k = 0; k < n_steps_dw; ++k) {
+            const tp_cblk_t& b = (k == own_slot_dw) ? own_blk : da_col_blocks[k];
+            if (int e = check_cblk(x_blocks_dw[k], sw.m)) return e;       // X block is [k = tokens][m = H_blk]
+            if (int e = check_cblk(b, sw.n)) return e;
+            pw.args.a[k] = x_blocks_dw[k].ptr; pw.args.lda[k] = (int32_t)x_blocks_dw[k].ld;
+            pw.args.b[k] = b.ptr; pw.args.ldb[k] = (int32_t)b.ld;
+        }
+        if (int e = check_oblk(dw, sw.n, true)) return e;
+        pw.args.out = dw.ptr; pw.args.ldo = dw.ld; pw.args.out_f32 = 1;
+        pw.form = FORM_TN; pw.plan = p;
+    }
+    size_t need = 0;
+    if (px.active) need = std::max(need, ws_bytes_for(px.plan, sx.m, sx.n));
+    if (pw.active) need = std::max(need, ws_bytes_for(pw.plan, sw.m, sw.n));
+    if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return TP_ERR_WORKSPACE;
+
+    // ---- launches (stream order: dA, db, dX, dW)
+    if (want_da) {
+        if (launch_dgelu(dy_own->ptr, dy_own->ld, preact_own->ptr, preact_own->ld, da_own_out.ptr, da_own_out.ld,
+                         sf.m, sf.n, stream) != hipSuccess) return TP_ERR_HIP;
+        if (db_f32 && launch_colsum(da_own_out.ptr, da_own_out.ld, sf.m, sf.n, static_cast<float*>(db_f32), stream) != hipSuccess)
+            return TP_ERR_HIP;
+    }
+    if (px.active) if (int e = run_product(px, workspace, stream)) return e;
+    if (pw.active) if (int e = run_product(pw, workspace, stream)) return e;
+    return TP_OK;
+}
+
+int tp_dgelu(const void* dy, int64_t ld_dy, const void* preact, int64_t ld_pre, void* da, int64_t ld_da,
+             int64_t rows, int64_t cols, void* hip_stream) {
+    if (!dy || !preact || !da) return TP_ERR_NULL;
+    if (rows < 0 || cols < 0) return TP_ERR_SHAPE;
+    if (!aligned16(dy) || !aligned16(preact) || !aligned16(da) || (cols & 7) || (ld_dy & 7) || (ld_pre & 7) || (ld_da & 7))
+        return TP_ERR_ALIGN;
+    if (ld_dy < cols || ld_pre < cols || ld_da < cols) return TP_ERR_SHAPE;
+    if (launch_dgelu(dy, ld_dy, preact, ld_pre, da, ld_da, rows, cols, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return TP_ERR_HIP;
+    return TP_OK;
+}
+
+int tp_plan_override(int key, int value) {
+    switch (key) {
+        case 0: if (value < 0 || value > TILE_128x128) return TP_ERR_MODE; g_tile_override = value; return TP_OK;
+        case 1: if (value < 0 || value > 8) return TP_ERR_MODE; g_split_override = value; return TP_OK;
+        case 2: if (value < 0 || value > 64) return TP_ERR_MODE; g_group_override = value; return TP_OK;
+        default: return TP_ERR_MODE;
+    }
+}
+
+const char* tp_strerror(int status) {
+    switch (status) {
+        case TP_OK: return "ok";
+        case TP_ERR_NULL: return "a required pointer is NULL";
+        case TP_ERR_MODE: return "unknown mode, pass, epilogue or option";
+        case TP_ERR_GRID: return "grid size or rank coordinate out of range";
+        case TP_ERR_SHAPE: return "layer dimensions, leading dimension or step count do not fit the grid";
+        case TP_ERR_ALIGN: return "pointer not 16-byte aligned, or a column extent / leading dimension not a multiple of 8";
+        case TP_ERR_DTYPE: return "output dtype not supported here";
+        case TP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case TP_ERR_HIP: return "a HIP call failed";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

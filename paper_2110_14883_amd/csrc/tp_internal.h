@@ -1,0 +1,56 @@
+// Internal interface between the C-ABI host code (tp_api.cpp) and the gfx950 kernels
+// (tp_kernels.hip).  Not installed; the public interface is include/tp_linear.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "tp_linear.h"
+
+namespace tpl {
+
+// Memory form of a product C[m,n] = sum_k A(m,k) B(k,n).  "kc" = the operand is stored with the
+// contraction index contiguous (A as [m][k], B as [n][k]); otherwise the other index is contiguous
+// (A as [k][m], B as [k][n]) and the tile is transposed on its way into LDS.
+enum GemmForm {
+    FORM_NN = 0,   // forward : A = X  [m][k] (kc),  B = W  [k][n]
+    FORM_NT = 1,   // dX      : A = dA [m][k] (kc),  B = W  [n][k] (kc)
+    FORM_TN = 2    // dW      : A = X  [k][m],       B = dA [k][n]
+};
+
+struct GemmArgs {
+    const void* a[TP_MAX_STEPS];
+    const void* b[TP_MAX_STEPS];
+    int32_t lda[TP_MAX_STEPS];   // elements
+    int32_t ldb[TP_MAX_STEPS];
+    int32_t M, N, K;             // output extents and the contraction length of ONE step
+    int32_t n_steps;
+    int32_t tiles_m, tiles_n;
+    int32_t split_k;             // >= 1; > 1 writes fp32 partials to ws
+    int32_t group_m;             // tile-order group height (tile rows)
+    // epilogue (used when split_k == 1)
+    void* out;   int64_t ldo;   int32_t out_f32;
+    void* pre;   int64_t ldp;           // optional bf16 copy of the pre-activation
+    const void* bias;                   // bf16 [N] or null
+    int32_t gelu;                       // apply erf-GeLU after the bias
+    const void* dg; int64_t lddg;       // optional bf16 [M][N]: multiply by GeLU'(dg)
+    float* ws;                          // [split_k][M][N] fp32 partials
+};
+
+struct ReduceArgs {
+    const float* ws; int32_t split_k; int32_t M, N;
+    void* out;   int64_t ldo;   int32_t out_f32;
+    void* pre;   int64_t ldp;
+    const void* bias; int32_t gelu;
+    const void* dg; int64_t lddg;
+};
+
+// tile ids: macro-tile shapes the GEMM kernel is instantiated for
+enum TileId { TILE_256x256 = 1, TILE_128x256 = 2, TILE_256x128 = 3, TILE_128x128 = 4 };
+void tile_shape(int tile_id, int* bm, int* bn);
+
+hipError_t launch_gemm(int form, int tile_id, const GemmArgs& args, hipStream_t stream);
+hipError_t launch_reduce(const ReduceArgs& args, hipStream_t stream);
+hipError_t launch_dgelu(const void* dy, int64_t ld_dy, const void* pre, int64_t ld_pre,
+                        void* da, int64_t ld_da, int64_t rows, int64_t cols, hipStream_t stream);
+hipError_t launch_colsum(const void* da, int64_t ld, int64_t rows, int64_t cols, float* out, hipStream_t stream);
+
+}  // namespace tpl

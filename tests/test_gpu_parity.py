@@ -1,0 +1,168 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle on the same seeded bits.
+Small shares are compared element by element (several tiles, ragged tails, every mode, every
+macro-tile, split K); the five benchmark shares are compared at full size on sampled output rows."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2110_14883_amd as T
+import synth_inputs as S
+from oracle import tp_oracle as O
+from paper_2110_14883_amd import workloads as WL
+
+from gpu_util import check, dev, f64, host64, overrides, run_share, say, workspace_for
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    T.lib()                       # fails loudly if the HIP library is not built
+
+
+SMALL = [
+    ("2d_q2", T.Grid(T.MODE_2D, q=2, ri=1, rj=0), (2 * 300, 2 * 136, 2 * 328)),
+    ("2d_q3", T.Grid(T.MODE_2D, q=3, ri=2, rj=1), (3 * 70, 3 * 64, 3 * 264)),
+    ("2p5d_q2_d2", T.Grid(T.MODE_2P5D, q=2, d=2, ri=1, rj=1, rk=1), (4 * 77, 2 * 72, 2 * 264)),
+    ("3d_p2", T.Grid(T.MODE_3D, p=2, ri=1, rj=0, rk=1), (4 * 130, 2 * 200, 2 * 520)),
+    ("1d_col_p3", T.Grid(T.MODE_1D_COL, p=3, ri=2), (270, 96, 3 * 264)),
+]
+
+
+@pytest.mark.parametrize("name,grid,dims", SMALL, ids=[s[0] for s in SMALL])
+def test_small_share_elementwise(name, grid, dims):
+    run_share(grid, dims, y_dtype="bf16", dx_dtype="bf16", want_db=True, label=name)
+    run_share(grid, dims, y_dtype="f32", dx_dtype="f32", label=name + " fp32 outputs", seed=77)
+    run_share(grid, dims, y_dtype="f32", dx_dtype="f32", use_own_slot=False, label=name + " ready-made dA", seed=78)
+
+
+@pytest.mark.parametrize("tile", [1, 2, 3, 4])
+@pytest.mark.parametrize("split", [1, 3])
+def test_every_tile_shape_and_split(tile, split):
+    grid, dims = T.Grid(T.MODE_2D, q=2, ri=0, rj=1), (2 * 300, 2 * 392, 2 * 328)
+    with overrides(tile=tile, split=split, group=3):
+        run_share(grid, dims, y_dtype="f32", dx_dtype="bf16", label=f"tile {tile} split {split}")
+
+
+def test_prefix_of_steps_and_bias_only():
+    grid, dims = T.Grid(T.MODE_3D, p=2, ri=1, rj=1, rk=0), (4 * 96, 2 * 128, 2 * 256)
+    run_share(grid, dims, n_steps=1, label="3d literal single step")
+    run_share(grid, dims, epi=T.EPI_BIAS, backward=False, y_dtype="f32", label="bias only")
+    run_share(grid, dims, epi=T.EPI_NONE, backward=False, y_dtype="f32", label="no epilogue")
+
+
+def test_degenerate_extents():
+    # one row, one 8-wide column block, K of one chunk
+    run_share(T.Grid(T.MODE_2D, q=1), (1, 8, 8), y_dtype="f32", dx_dtype="f32", label="1x8x8")
+    run_share(T.Grid(T.MODE_2D, q=2, ri=1, rj=1), (2, 16, 16), label="q2 of 2x16x16")
+    run_share(T.Grid(T.MODE_1D_COL, p=1), (257, 72, 8), y_dtype="f32", label="257x72x8")
+
+
+def test_gelu_tails_and_strided_blocks():
+    """Pre-activations far in both tails, and blocks that are views with ld > cols."""
+    m, n = 64, 256
+    a = np.linspace(-12.0, 12.0, m * n).reshape(m, n)
+    a_bits = O.f64_to_bf16_bits(O.round_to_bf16(a))
+    g_bits = S.normal_block_bf16(5, S.T_G, n, 0, m, 0, n, 1.0)
+    big_a = torch.zeros((m, n + 64), dtype=torch.bfloat16, device="cuda")
+    big_g = torch.zeros((m, n + 32), dtype=torch.bfloat16, device="cuda")
+    big_o = torch.zeros((m, n + 8), dtype=torch.bfloat16, device="cuda")
+    big_a[:, :n] = dev(a_bits)
+    big_g[:, 32:] = dev(g_bits)
+    T.tp_dgelu(big_g[:, 32:], big_a[:, :n], big_o[:, 8:])
+    torch.cuda.synchronize()
+    check(host64(big_o[:, 8:]), O.share_da(f64(g_bits), f64(a_bits)), "bf16", "dgelu over [-12, 12]")
+    assert float(big_o[:, :8].abs().max()) == 0.0
+    # forward with X = a (K = n), W = I block: Y = GeLU(a + b)
+    eye = torch.eye(n, dtype=torch.bfloat16, device="cuda")
+    bias = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    y = torch.empty((m, n), dtype=torch.float32, device="cuda")
+    T.tp_linear_fwd(T.Grid(T.MODE_2D, q=1), (m, n, n), 1, [big_a[:, :n]], [eye], bias, T.EPI_BIAS_GELU, y, None, None)
+    torch.cuda.synchronize()
+    check(host64(y), O.gelu(f64(a_bits)), "f32", "GeLU over [-12, 12]")
+    neg = f64(a_bits) < -3
+    rel = np.abs(host64(y)[neg] - O.gelu(f64(a_bits))[neg]) / np.abs(O.gelu(f64(a_bits))[neg])
+    say(f"    negative-tail relative error of GeLU (fp32 out): max {rel.max():.3g}")
+
+
+def test_mlp1d_chain_small():
+    _mlp1d(2, 1, 200, 136, 2 * 264, rows=None)
+    _mlp1d(3, 0, 520, 264, 3 * 72, rows=None)
+
+
+def _mlp1d(size, rank, M, H, F, rows, w_rows=None):
+    chained = False
+    say(f"[case] 1D chain size={size} rank={rank} M={M} H={H} F={F}")
+    inp = WL.make_mlp1d_inputs(size, rank, M, H, F)
+    fb = inp["fb"]
+    g1, d1 = T.Grid(T.MODE_1D_COL, p=size, ri=rank), (M, H, F)
+    g2, d2 = T.Grid(T.MODE_1D_ROW, p=size, ri=rank), (M, F, H)
+    X, W1, b1, W2, G = (dev(inp[k]) for k in ("X", "W1", "b1", "W2", "G"))
+    X64, W164, b164, W264, G64 = (f64(inp[k]) for k in ("X", "W1", "b1", "W2", "G"))
+    ws = workspace_for(g1, d1)
+    ws2 = workspace_for(g2, d2)
+    sel = slice(None) if rows is None else rows
+    wsel = slice(None) if w_rows is None else w_rows
+    fw = O.mlp1d_fwd(X64, W164, b164, W264)            # full: backward needs every row of A_saved and Z
+    Z = torch.empty((M, fb), dtype=torch.bfloat16, device="cuda")
+    A = torch.empty((M, fb), dtype=torch.bfloat16, device="cuda")
+    Y = torch.empty((M, H), dtype=torch.float32, device="cuda")
+    say("  fc1 fwd")
+    T.tp_linear_fwd(g1, d1, 1, [X], [W1], b1, T.EPI_BIAS_GELU, Z, A, ws)
+    torch.cuda.synchronize()
+    check(host64(Z[sel]), fw["Z"][sel], "bf16", "Z")
+    check(host64(A[sel]), fw["A_saved"][sel], "bf16", "A_saved")
+    Z_in = Z if chained else dev(O.f64_to_bf16_bits(fw["Z"]))
+    A_in = A if chained else dev(O.f64_to_bf16_bits(fw["A_saved"]))
+    say("  fc2 fwd")
+    T.tp_linear_fwd(g2, d2, 1, [Z_in], [W2], None, T.EPI_NONE, Y, None, ws2)
+    torch.cuda.synchronize()
+    if chained:          # Z differs from the oracle's by bf16 steps in places: compare at bf16 level
+        check(host64(Y[sel]), fw["Y"][sel], "bf16", "Y partial (chained)")
+    else:
+        check(host64(Y[sel]), fw["Y"][sel], "f32", "Y partial")
+    bw = O.mlp1d_bwd(X64, W164, W264, fw["A_saved"], fw["Z"], G64, rows=rows, w_rows=w_rows)
+    dA = torch.empty((M, fb), dtype=torch.bfloat16, device="cuda")
+    dW2 = torch.empty((fb, H), dtype=torch.float32, device="cuda")
+    say("  fc2 bwd (dZ with GeLU' epilogue, dW2)")
+    T.tp_linear_bwd(g2, d2, 1, 1, da_row_blocks=[G], w_blocks_dx=[W2], x_blocks_dw=[Z_in], da_col_blocks=[G],
+                    dgelu_preact=A_in, dx=dA, dw=dW2, workspace=ws2)
+    torch.cuda.synchronize()
+    check(host64(dA[sel]), bw["dA"], "bf16", "dA")
+    check(host64(dW2[wsel]), bw["dW2"], "bf16" if chained else "f32", "dW2")
+    if chained:
+        dA_in = dA
+    else:
+        full = O.mlp1d_bwd(X64, W164, W264, fw["A_saved"], fw["Z"], G64)["dA"] if rows is not None else bw["dA"]
+        dA_in = dev(O.f64_to_bf16_bits(full))
+    dX = torch.empty((M, H), dtype=torch.float32, device="cuda")
+    dW1 = torch.empty((H, fb), dtype=torch.float32, device="cuda")
+    say("  fc1 bwd (dX partial, dW1)")
+    T.tp_linear_bwd(g1, d1, 1, 1, da_row_blocks=[dA_in], w_blocks_dx=[W1], x_blocks_dw=[X], da_col_blocks=[dA_in],
+                    dx=dX, dw=dW1, workspace=ws)
+    torch.cuda.synchronize()
+    check(host64(dX[sel]), bw["dX"], "bf16" if chained else "f32", "dX partial")
+    check(host64(dW1[wsel]), bw["dW1"], "bf16" if chained else "f32", "dW1")
+
+
+# ----------------------------------------------------------------------------- the benchmark shares at full size
+def test_config1_full():
+    c = WL.config("c1_2d_q2_fwd")
+    run_share(c.grid, c.dims, y_dtype="f32", backward=False, label=c.name)
+
+
+@pytest.mark.parametrize("name", ["c3_2d_q4", "c4_2p5d_q2_d2", "c5_3d_p2", "c5x_3d_p2_exact"])
+def test_config_full_size_sampled(name):
+    c = WL.config(name)
+    mp = T.tp_block_map(c.grid, c.dims, 0)
+    rows = S.sample_rows(3, mp["m"], 192)
+    w_rows = S.sample_rows(4, mp["k"], 96)
+    run_share(c.grid, c.dims, n_steps=c.n_steps, rows=rows, w_rows=w_rows, synthetic_preact=True, label=name)
+
+
+def test_config2_full_size_sampled():
+    c = WL.config("c2_1d_n4_mlp")
+    M, H, F = c.dims
+    _mlp1d(c.grid.p, c.grid.ri, M, H, F, rows=S.sample_rows(5, M, 192),
+           w_rows=S.sample_rows(6, H, 96))

@@ -1,0 +1,149 @@
+"""Host-side checks that need no GPU: the C-ABI library loads and exports every symbol the header
+declares, its partition map agrees with the oracle's independently written one, and invalid
+arguments come back as status codes."""
+import ctypes as C
+import itertools
+import os
+import re
+
+import pytest
+
+import paper_2110_14883_amd as T
+from oracle import tp_oracle as O
+from paper_2110_14883_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "tp_linear.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(tp_[a-z_0-9]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    L = T.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_strerror_texts():
+    assert T.tp_strerror(0) == "ok"
+    assert len({T.tp_strerror(i) for i in range(9)}) == 9
+    assert "unknown" in T.tp_strerror(1234)
+
+
+def _pairs():
+    out = []
+    for n in (1, 2, 3, 4):
+        for r in range(n):
+            out.append((T.Grid(T.MODE_1D_COL, p=n, ri=r), O.Grid(O.MODE_1D_COL, p=n, ri=r)))
+            out.append((T.Grid(T.MODE_1D_ROW, p=n, ri=r), O.Grid(O.MODE_1D_ROW, p=n, ri=r)))
+    for q in (1, 2, 3, 4):
+        for i, j in itertools.product(range(q), range(q)):
+            out.append((T.Grid(T.MODE_2D, q=q, ri=i, rj=j), O.Grid(O.MODE_2D, q=q, ri=i, rj=j)))
+            for d in (1, 2, 3):
+                for l in range(d):
+                    out.append((T.Grid(T.MODE_2P5D, q=q, d=d, ri=i, rj=j, rk=l),
+                                O.Grid(O.MODE_2P5D, q=q, d=d, ri=i, rj=j, rk=l)))
+    for p in (1, 2, 3):
+        for i, j, l in itertools.product(range(p), range(p), range(p)):
+            out.append((T.Grid(T.MODE_3D, p=p, ri=i, rj=j, rk=l), O.Grid(O.MODE_3D, p=p, ri=i, rj=j, rk=l)))
+    return out
+
+
+def test_block_map_agrees_with_the_oracle_map():
+    M, H, F = 8 * 36, 8 * 12, 8 * 24
+    for tg, og in _pairs():
+        rc, kc, cc = O.chunk_counts(og)
+        for pass_ in (0, 1, 2):
+            got = T.tp_block_map(tg, (M, H, F), pass_)
+            ref = O.block_map(og, pass_)
+            assert got["a"] == ref["a"] and got["b"] == ref["b"], (og, pass_)
+            assert got["out"] == ref["out"] and got["partial"] == ref["partial"], (og, pass_)
+            mb, hb, fb = M // rc, H // kc, F // cc
+            assert (got["m"], got["n"], got["k"]) == {0: (mb, fb, hb), 1: (mb, hb, fb), 2: (hb, fb, mb)}[pass_]
+
+
+def test_config_block_shapes():
+    """The five benchmark shares have the local extents their descriptions state."""
+    from paper_2110_14883_amd import workloads as WL
+    exp = {"c1_2d_q2_fwd": (128, 2048, 512, 2), "c3_2d_q4": (2048, 8192, 2048, 4),
+           "c4_2p5d_q2_d2": (32896, 2560, 640, 2), "c5_3d_p2": (4096, 24576, 6144, 2)}
+    for name, (m, n, k, s) in exp.items():
+        c = WL.config(name)
+        mp = T.tp_block_map(c.grid, c.dims, 0)
+        assert (mp["m"], mp["n"], mp["k"], mp["n_steps"]) == (m, n, k, s)
+    c = WL.config("c2_1d_n4_mlp")
+    mp = T.tp_block_map(c.grid, c.dims, 0)
+    assert (mp["m"], mp["n"], mp["k"]) == (16384, 4096, 4096)
+    assert WL.gemm_flops(c)["total"] == pytest.approx(3.299e12, rel=1e-3)
+    assert WL.gemm_flops(WL.config("c3_2d_q4"))["total"] == pytest.approx(8.246e11, rel=1e-3)
+    assert WL.gemm_flops(WL.config("c4_2p5d_q2_d2"))["total"] == pytest.approx(6.468e11, rel=1e-3)
+    assert WL.gemm_flops(WL.config("c5_3d_p2"))["total"] == pytest.approx(3.711e12, rel=1e-3)
+
+
+def _st(fn):
+    try:
+        fn()
+    except T.TpError as e:
+        return e.status
+    return 0
+
+
+def test_grid_and_shape_errors():
+    d = (64, 64, 64)
+    assert _st(lambda: T.tp_block_map(T.Grid(99), d, 0)) == 2
+    assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_2D, q=2), d, 7)) == 2
+    assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_2D, q=2, ri=2), d, 0)) == 3
+    assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_2D, q=0), d, 0)) == 3
+    assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_2D, q=2, d=2), d, 0)) == 3       # depth is not a 2D notion
+    assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_2P5D, q=2, d=2, rk=2), d, 0)) == 3
+    assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_3D, p=3), d, 0)) == 4             # 64 % 9
+    assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_2D, q=32), (64, 64, 64), 0)) == 3  # more steps than TP_MAX_STEPS
+    assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_1D_COL, p=3), d, 0)) == 4
+    assert T.tp_linear_workspace_size(T.Grid(T.MODE_2D, q=2, ri=5), d, 0) == 0
+
+
+def test_argument_errors_before_any_launch():
+    """Every rejection happens on the host: fake (never dereferenced) device addresses suffice."""
+    g, d = T.Grid(T.MODE_2D, q=2), (256, 128, 256)       # local m=128, k=64, n=128
+    good = (0x10000, 64)
+    y = (0x20000, 128, B.DT_F32)
+    none_o = (0, 0, 0)
+    call = lambda **kw: T.tp_linear_fwd(g, d, kw.get("n_steps", 2), kw.get("x", [good, good]), kw.get("w", [(0x30000, 128)] * 2),
+                                        kw.get("bias", 0x40000), kw.get("epi", T.EPI_BIAS_GELU), kw.get("y", y),
+                                        kw.get("pre", none_o), None, stream=0)
+    assert _st(lambda: call(n_steps=3)) == 4
+    assert _st(lambda: call(n_steps=0)) == 4
+    assert _st(lambda: call(x=[good, (0, 64)])) == 1
+    assert _st(lambda: call(x=[good, (0x10008, 64)])) == 5
+    assert _st(lambda: call(x=[good, (0x10000, 60)])) == 5
+    assert _st(lambda: call(x=[good, (0x10000, 56)])) == 4          # ld smaller than the block
+    assert _st(lambda: call(bias=0)) == 1
+    assert _st(lambda: call(epi=9)) == 2
+    assert _st(lambda: call(y=(0x20000, 128, 5))) == 6
+    assert _st(lambda: call(y=none_o)) == 1
+    assert _st(lambda: call(pre=(0x50000, 128, B.DT_F32))) == 6
+    # odd column extents cannot be loaded 128 bits at a time
+    assert _st(lambda: T.tp_linear_fwd(T.Grid(T.MODE_2D, q=2), (256, 128, 2 * 100), 2, [good, good],
+                                       [(0x30000, 104)] * 2, 0x40000, T.EPI_BIAS, (0x20000, 104, B.DT_F32),
+                                       none_o, None, stream=0)) == 5
+    # backward: dW must be fp32, db and own slots need the dA this call computes
+    bw = lambda **kw: T.tp_linear_bwd(g, d, 2, 2, da_row_blocks=[(0x10000, 128)] * 2, w_blocks_dx=[(0x30000, 128)] * 2,
+                                      x_blocks_dw=[good, good], da_col_blocks=[(0x10000, 128)] * 2, stream=0, **kw)
+    assert _st(lambda: bw(dw=(0x60000, 128, B.DT_BF16))) == 6
+    assert _st(lambda: bw(dx=(0x60000, 64, B.DT_BF16), own_slot_dx=0)) == 1
+    assert _st(lambda: bw(dx=(0x60000, 64, B.DT_BF16), db=0x70000)) == 1
+    assert _st(lambda: T.tp_dgelu((0x10000, 0), (0x10000, 0), (0x10000, 0), 4, 12, stream=0)) in (4, 5)
+    assert _st(lambda: T.tp_plan_override(9, 0)) == 2
+    assert _st(lambda: T.tp_plan_override(1, 99)) == 2
+
+
+def test_workspace_size_bounds():
+    from paper_2110_14883_amd import workloads as WL
+    for c in WL.CONFIGS:
+        for pass_ in (0, 1, 2):
+            mp = T.tp_block_map(c.grid, c.dims, pass_)
+            ws = T.tp_linear_workspace_size(c.grid, c.dims, pass_)
+            assert ws <= 8 * mp["m"] * mp["n"] * 4
+    # a share with one output tile and a long contraction must split K
+    assert T.tp_linear_workspace_size(T.Grid(T.MODE_2D, q=1), (256, 65536, 256), 0) > 0
