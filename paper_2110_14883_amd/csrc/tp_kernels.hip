@@ -223,7 +223,7 @@ __device__ __forceinline__ void tile_of_block(const GemmArgs& p, int& tm, int& t
 // ---------------------------------------------------------------------------------------------
 // the GEMM kernel
 // ---------------------------------------------------------------------------------------------
-template <int BM, int BN, bool A_KC, bool B_KC>
+template <int BM, int BN, bool A_KC, bool B_KC, int PF, bool PRIO>
 __global__ __launch_bounds__(NTHREADS) void tp_gemm_kernel(const GemmArgs p) {
     constexpr int TM = BM / 64;      // 32-row MFMA tiles per wave along M (2 waves along M)
     constexpr int TN = BN / 128;     // 32-col MFMA tiles per wave along N (4 waves along N)
@@ -244,22 +244,24 @@ __global__ __launch_bounds__(NTHREADS) void tp_gemm_kernel(const GemmArgs p) {
     const int Z = p.split_k;
     const int my_tiles = (T - z + Z - 1) / Z;       // tiles z, z+Z, ... (every step is visited)
 
-    typename std::conditional<A_KC, StageKC<BM>, StageXC<BM>>::type sa;
-    typename std::conditional<B_KC, StageKC<BN>, StageXC<BN>>::type sb;
+    using StageA = typename std::conditional<A_KC, StageKC<BM>, StageXC<BM>>::type;
+    using StageB = typename std::conditional<B_KC, StageKC<BN>, StageXC<BN>>::type;
+    StageA sa[PF];
+    StageB sb[PF];
 
-    auto fetch = [&](int tile) {
+    auto fetch = [&](int tile, StageA& qa, StageB& qb) {
         const int s = tile / KT;
         const int k0 = (tile - s * KT) * BK;
         const uint16_t* ap = static_cast<const uint16_t*>(p.a[s]);
         const uint16_t* bp = static_cast<const uint16_t*>(p.b[s]);
-        if constexpr (A_KC) sa.load(ap, p.lda[s], p.M, m0, p.K, k0, t);
-        else                sa.load(ap, p.lda[s], p.K, k0, p.M, m0, t);
-        if constexpr (B_KC) sb.load(bp, p.ldb[s], p.N, n0, p.K, k0, t);
-        else                sb.load(bp, p.ldb[s], p.K, k0, p.N, n0, t);
+        if constexpr (A_KC) qa.load(ap, p.lda[s], p.M, m0, p.K, k0, t);
+        else                qa.load(ap, p.lda[s], p.K, k0, p.M, m0, t);
+        if constexpr (B_KC) qb.load(bp, p.ldb[s], p.N, n0, p.K, k0, t);
+        else                qb.load(bp, p.ldb[s], p.K, k0, p.N, n0, t);
     };
-    auto stash = [&](int buf) {
-        sa.store(lds + buf * STAGE_BYTES, t);
-        sb.store(lds + buf * STAGE_BYTES + A_BYTES, t);
+    auto stash = [&](int buf, const StageA& qa, const StageB& qb) {
+        qa.store(lds + buf * STAGE_BYTES, t);
+        qb.store(lds + buf * STAGE_BYTES + A_BYTES, t);
     };
 
     f32x16_t acc[TM][TN];
@@ -275,17 +277,10 @@ __global__ __launch_bounds__(NTHREADS) void tp_gemm_kernel(const GemmArgs p) {
     const int rb = wn * (BN / 4) + (l & 31);
     const int ch = l >> 5;
 
-    fetch(z);
-    stash(0);
-    __syncthreads();
-
-    for (int i = 0; i < my_tiles; ++i) {
-        const int cur = i & 1;
-        const bool more = (i + 1) < my_tiles;
-        if (more) fetch(z + (i + 1) * Z);
-
+    auto compute = [&](int cur) {
         const char* la = lds + cur * STAGE_BYTES;
         const char* lb = la + A_BYTES;
+        if constexpr (PRIO) __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8_t fa[TM], fb[TN];
@@ -301,13 +296,255 @@ __global__ __launch_bounds__(NTHREADS) void tp_gemm_kernel(const GemmArgs p) {
                 for (int j = 0; j < TN; ++j)
                     acc[i2][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i2], acc[i2][j], 0, 0, 0);
         }
+        if constexpr (PRIO) __builtin_amdgcn_s_setprio(0);
+    };
 
-        if (more) stash(cur ^ 1);
+    if constexpr (PF == 1) {
+        // the tile after the current one travels through registers while the current one is multiplied
+        fetch(z, sa[0], sb[0]);
+        stash(0, sa[0], sb[0]);
         __syncthreads();
+        for (int i = 0; i < my_tiles; ++i) {
+            const int cur = i & 1;
+            const bool more = (i + 1) < my_tiles;
+            if (more && (p.dbg == 0 || p.dbg == 3)) fetch(p.dbg == 3 ? z : z + (i + 1) * Z, sa[0], sb[0]);
+            compute(cur);
+            if (more && p.dbg < 2) stash(cur ^ 1, sa[0], sb[0]);
+            __syncthreads();
+        }
+    } else {
+        // two tiles in flight: tile i+1 waits in one register set (fetched an iteration ago) while
+        // tile i+2 is being fetched into the other
+        fetch(z, sa[0], sb[0]);
+        stash(0, sa[0], sb[0]);
+        if (my_tiles > 1) fetch(z + Z, sa[0], sb[0]);
+        __syncthreads();
+        for (int i = 0; i < my_tiles; i += 2) {
+            // even iteration: LDS buffer 0 is current, set 0 holds tile i+1, set 1 receives tile i+2
+            if (i + 2 < my_tiles) fetch(z + (i + 2) * Z, sa[1], sb[1]);
+            compute(0);
+            if (i + 1 < my_tiles) stash(1, sa[0], sb[0]);
+            __syncthreads();
+            if (i + 1 >= my_tiles) break;
+            // odd iteration: buffer 1 is current, set 1 holds tile i+2, set 0 receives tile i+3
+            if (i + 3 < my_tiles) fetch(z + (i + 3) * Z, sa[0], sb[0]);
+            compute(1);
+            if (i + 2 < my_tiles) stash(0, sa[1], sb[1]);
+            __syncthreads();
+        }
     }
 
     // ------------------------------------------------------------------ epilogue
     // acc[i][j][v]: row m = 32 i + lane%32, columns n = 32 j + 8 (v/4) + 4 (lane/32) + v%4
+    if (Z > 1) {
+        float* wsz = p.ws + (int64_t)z * p.M * p.N;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m = m0 + wm * (BM / 2) + 32 * i + (l & 31);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n0 + wn * (BN / 4) + 32 * j + 8 * g + 4 * ch;
+                    if (m < p.M && n < p.N) {
+                        f32x4_t s = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                        *reinterpret_cast<f32x4_t*>(wsz + (int64_t)m * p.N + n) = s;
+                    }
+                }
+        }
+        return;
+    }
+    Epilogue e{p.out, p.ldo, p.out_f32, p.pre, p.ldp, p.bias, p.gelu, p.dg, p.lddg};
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = m0 + wm * (BM / 2) + 32 * i + (l & 31);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + wn * (BN / 4) + 32 * j + 8 * g + 4 * ch;
+                if (m < p.M && n < p.N) {
+                    float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                    epilogue4(e, v, m, n);
+                }
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Ping-pong variant.  Waves 0-3 ("P", one per SIMD) stage operand A, waves 4-7 ("Q") stage operand
+// B, each with 256 threads.  Inside one K tile P multiplies first and refills LDS afterwards, Q
+// refills first and multiplies afterwards, so on every SIMD one wave has MFMAs ready while the
+// other one is busy with global loads and LDS writes.  One workgroup barrier per K tile.
+// ---------------------------------------------------------------------------------------------
+// swizzle that keeps both the fragment reads (16 consecutive rows, one chunk) and the transposed
+// 128-bit writes (rows 8 apart, one chunk) free of bank conflicts
+__device__ __forceinline__ uint32_t lds_off2(int r, int c) {
+    return (uint32_t)(((r << 3) + (c ^ (((r >> 1) & 7) ^ ((r >> 4) & 3)))) << 4);
+}
+
+// contraction-contiguous operand staged by 256 threads: chunk c = tg%8 of rows tg/8 + 32 i
+template <int R>
+struct HalfKC {
+    static constexpr int NCH = R / 32;
+    u32x4_t reg[NCH];
+    __device__ __forceinline__ void load(const uint16_t* ptr, int ld, int rows, int row0, int K, int k0, int tg) {
+        const int c = tg & 7, r0 = tg >> 3;
+        const uint16_t* base = ptr + (int64_t)row0 * ld + k0;
+        const int64_t rem = ((int64_t)(rows - row0 - 1) * ld + (K - k0)) * 2;
+        __amdgpu_buffer_rsrc_t rs = make_rsrc(base, rem);
+        const bool kok = (k0 + c * 8) < K;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const uint32_t off = (uint32_t)(((r0 + 32 * i) * ld + c * 8) * 2);
+            reg[i] = buf_load16(rs, kok ? off : OOB_OFFSET);
+        }
+    }
+    __device__ __forceinline__ void store(char* lds, int tg) const {
+        const int c = tg & 7, r0 = tg >> 3;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i)
+            *reinterpret_cast<u32x4_t*>(lds + lds_off2(r0 + 32 * i, c)) = reg[i];
+    }
+};
+
+// operand stored [k][x]: one 8 (k) x 8 (x) block per thread, transposed with byte permutes and
+// written as 8 rows of 8 consecutive k (128-bit writes).  R = 256 uses all 256 threads, R = 128 half.
+template <int R>
+struct HalfXC {
+    static constexpr int XB = R / 8;            // x blocks per tile
+    u32x4_t reg[8];
+    __device__ __forceinline__ void load(const uint16_t* ptr, int ld, int krows, int k0, int X, int x0, int tg) {
+        const int x = (tg % XB) * 8, k = (tg / XB) * 8;
+        const uint16_t* base = ptr + (int64_t)k0 * ld + x0;
+        const int64_t rem = ((int64_t)(krows - k0 - 1) * ld + (X - x0)) * 2;
+        __amdgpu_buffer_rsrc_t rs = make_rsrc(base, rem);
+        const bool ok = (x0 + x) < X && k < BK;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t off = (uint32_t)(((k + i) * ld + x) * 2);
+            reg[i] = buf_load16(rs, ok ? off : OOB_OFFSET);
+        }
+    }
+    __device__ __forceinline__ void store(char* lds, int tg) const {
+        const int x = (tg % XB) * 8, k = (tg / XB) * 8;
+        if (k >= BK) return;
+        const int c = k >> 3;
+#pragma unroll
+        for (int wd = 0; wd < 4; ++wd) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const uint32_t sel = e ? 0x07060302u : 0x05040100u;
+                u32x4_t v = {__builtin_amdgcn_perm(reg[1][wd], reg[0][wd], sel), __builtin_amdgcn_perm(reg[3][wd], reg[2][wd], sel),
+                             __builtin_amdgcn_perm(reg[5][wd], reg[4][wd], sel), __builtin_amdgcn_perm(reg[7][wd], reg[6][wd], sel)};
+                *reinterpret_cast<u32x4_t*>(lds + lds_off2(x + 2 * wd + e, c)) = v;
+            }
+        }
+    }
+};
+
+template <int BM, int BN, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(NTHREADS) void tp_gemm_pp_kernel(const GemmArgs p) {
+    constexpr int TM = BM / 64;
+    constexpr int TN = BN / 128;
+    constexpr int A_BYTES = BM * BK * 2;
+    constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    const int t = threadIdx.x;
+    const int l = t & 63, w = __builtin_amdgcn_readfirstlane(t >> 6);     // wave index, known uniform
+    const int wm = w & 1, wn = ((w >> 1) & 1) | ((w >> 2) << 1);          // P waves: wn in {0,1}; Q waves: wn in {2,3}
+    const bool is_p = w < 4;
+    const int tg = t & 255;
+
+    int tile_m, tile_n, z;
+    tile_of_block(p, tile_m, tile_n, z);
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int KT = (p.K + BK - 1) / BK;
+    const int T = p.n_steps * KT;
+    const int Z = p.split_k;
+    const int my_tiles = (T - z + Z - 1) / Z;
+
+    using StageA = typename std::conditional<A_KC, HalfKC<BM>, HalfXC<BM>>::type;
+    using StageB = typename std::conditional<B_KC, HalfKC<BN>, HalfXC<BN>>::type;
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const int ra = wm * (BM / 2) + (l & 31);
+    const int rb = wn * (BN / 4) + (l & 31);
+    const int ch = l >> 5;
+
+    auto compute = [&](int cur) {
+        const char* la = lds + cur * STAGE_BYTES;
+        const char* lb = la + A_BYTES;
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8_t fa[TM], fb[TN];
+#pragma unroll
+            for (int i2 = 0; i2 < TM; ++i2)
+                fa[i2] = *reinterpret_cast<const bf16x8_t*>(la + lds_off2(ra + 32 * i2, 2 * ks + ch));
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                fb[j] = *reinterpret_cast<const bf16x8_t*>(lb + lds_off2(rb + 32 * j, 2 * ks + ch));
+#pragma unroll
+            for (int i2 = 0; i2 < TM; ++i2)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i2][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i2], acc[i2][j], 0, 0, 0);
+        }
+        __builtin_amdgcn_s_setprio(0);
+    };
+
+    if (is_p) {
+        StageA sa;
+        auto fetch = [&](int tile) {
+            const int s = tile / KT;
+            const int k0 = (tile - s * KT) * BK;
+            const uint16_t* ap = static_cast<const uint16_t*>(p.a[s]);
+            if constexpr (A_KC) sa.load(ap, p.lda[s], p.M, m0, p.K, k0, tg);
+            else                sa.load(ap, p.lda[s], p.K, k0, p.M, m0, tg);
+        };
+        fetch(z);
+        sa.store(lds, tg);
+        if (my_tiles > 1) fetch(z + Z);
+        __syncthreads();
+        for (int i = 0; i < my_tiles; ++i) {
+            const int cur = i & 1;
+            compute(cur);
+            if (i + 1 < my_tiles && p.dbg != 2) sa.store(lds + (cur ^ 1) * STAGE_BYTES, tg);
+            if (i + 2 < my_tiles && (p.dbg == 0 || p.dbg == 3)) fetch(p.dbg == 3 ? z : z + (i + 2) * Z);
+            __syncthreads();
+        }
+    } else {
+        StageB sb;
+        auto fetch = [&](int tile) {
+            const int s = tile / KT;
+            const int k0 = (tile - s * KT) * BK;
+            const uint16_t* bp = static_cast<const uint16_t*>(p.b[s]);
+            if constexpr (B_KC) sb.load(bp, p.ldb[s], p.N, n0, p.K, k0, tg);
+            else                sb.load(bp, p.ldb[s], p.K, k0, p.N, n0, tg);
+        };
+        fetch(z);
+        sb.store(lds + A_BYTES, tg);
+        if (my_tiles > 1) fetch(z + Z);
+        __syncthreads();
+        for (int i = 0; i < my_tiles; ++i) {
+            const int cur = i & 1;
+            if (i + 1 < my_tiles && p.dbg != 2) sb.store(lds + (cur ^ 1) * STAGE_BYTES + A_BYTES, tg);
+            if (i + 2 < my_tiles && (p.dbg == 0 || p.dbg == 3)) fetch(p.dbg == 3 ? z : z + (i + 2) * Z);
+            compute(cur);
+            __syncthreads();
+        }
+    }
+
+    // ------------------------------------------------------------------ epilogue (as in tp_gemm_kernel)
     if (Z > 1) {
         float* wsz = p.ws + (int64_t)z * p.M * p.N;
 #pragma unroll
@@ -424,28 +661,56 @@ void tile_shape(int tile_id, int* bm, int* bn) {
     }
 }
 
-template <int BM, int BN, bool A_KC, bool B_KC>
+template <int BM, int BN, bool A_KC, bool B_KC, int PF, bool PRIO>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
     constexpr int lds_bytes = 2 * (BM + BN) * BK * 2;
     static bool attr_set = false;           // same value every time: a repeated set is harmless
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tp_gemm_kernel<BM, BN, A_KC, B_KC>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tp_gemm_kernel<BM, BN, A_KC, B_KC, PF, PRIO>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const unsigned grid = (unsigned)(a.tiles_m * a.tiles_n * a.split_k);
-    hipLaunchKernelGGL((tp_gemm_kernel<BM, BN, A_KC, B_KC>), dim3(grid), dim3(NTHREADS), lds_bytes, stream, a);
+    hipLaunchKernelGGL((tp_gemm_kernel<BM, BN, A_KC, B_KC, PF, PRIO>), dim3(grid), dim3(NTHREADS), lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, bool A_KC, bool B_KC>
+static hipError_t launch_pp(const GemmArgs& a, hipStream_t stream) {
+    constexpr int lds_bytes = 2 * (BM + BN) * BK * 2;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tp_gemm_pp_kernel<BM, BN, A_KC, B_KC>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const unsigned grid = (unsigned)(a.tiles_m * a.tiles_n * a.split_k);
+    hipLaunchKernelGGL((tp_gemm_pp_kernel<BM, BN, A_KC, B_KC>), dim3(grid), dim3(NTHREADS), lds_bytes, stream, a);
     return hipGetLastError();
 }
 
 template <bool A_KC, bool B_KC>
 static hipError_t launch_form(int tile_id, const GemmArgs& a, hipStream_t s) {
+    if (a.variant == 0) {
+        switch (tile_id) {
+            case TILE_256x256: return launch_pp<256, 256, A_KC, B_KC>(a, s);
+            case TILE_128x256: return launch_pp<128, 256, A_KC, B_KC>(a, s);
+            case TILE_256x128: return launch_pp<256, 128, A_KC, B_KC>(a, s);
+            case TILE_128x128: return launch_pp<128, 128, A_KC, B_KC>(a, s);
+            default: return hipErrorInvalidValue;
+        }
+    }
     switch (tile_id) {
-        case TILE_256x256: return launch_one<256, 256, A_KC, B_KC>(a, s);
-        case TILE_128x256: return launch_one<128, 256, A_KC, B_KC>(a, s);
-        case TILE_256x128: return launch_one<256, 128, A_KC, B_KC>(a, s);
-        case TILE_128x128: return launch_one<128, 128, A_KC, B_KC>(a, s);
+        case TILE_256x256:
+            switch (a.variant) {
+                case 2: return launch_one<256, 256, A_KC, B_KC, 1, true>(a, s);
+                default: return launch_one<256, 256, A_KC, B_KC, 1, false>(a, s);
+            }
+        case TILE_128x256: return launch_one<128, 256, A_KC, B_KC, 1, false>(a, s);
+        case TILE_256x128: return launch_one<256, 128, A_KC, B_KC, 1, false>(a, s);
+        case TILE_128x128: return launch_one<128, 128, A_KC, B_KC, 1, false>(a, s);
         default: return hipErrorInvalidValue;
     }
 }
