@@ -30,9 +30,13 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0          # MI355X dense bf16 MFMA peak (published figure, 2.5 PFLOP/s)
 NSETS = 3                          # buffer sets rotated through, so nothing is re-served from the 256 MB MALL
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (scaled by a copy kernel of known size); None until such a run has been summarised in profiles/.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM-side bytes per launch (read + written) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# summarised in profiles/gemm_256x256_config2_1d_mlp.md (scaled there by a copy of known size).
+MEASURED_TRAFFIC_BYTES = {
+    "tpl::tp_gemm_kernel<256, 256, true, false>": 1338467739,
+    "tpl::tp_gemm_kernel<256, 256, true, true>": 1305676211,
+    "tpl::tp_gemm_kernel<256, 256, false, false>": 897679149,
+}
 
 
 def log(*a):
@@ -213,8 +217,8 @@ def main() -> int:
     flops_per_launch = main_res["gemm_flops"] / sum(len(v) for v in by_form.values())
     avg_ms = sum(c["ms"] for c in lst) / len(lst)
     achieved = flops_per_launch / avg_ms / 1e9
-    kname = {"NN": "tp_gemm_kernel<256,256,true,false>", "NT": "tp_gemm_kernel<256,256,true,true>",
-             "TN": "tp_gemm_kernel<256,256,false,false>"}[form]
+    kname = {"NN": "tpl::tp_gemm_kernel<256, 256, true, false>", "NT": "tpl::tp_gemm_kernel<256, 256, true, true>",
+             "TN": "tpl::tp_gemm_kernel<256, 256, false, false>"}[form]
     roofline = dict(bound="mfma", kernel=kname, launches_per_step=len(lst), avg_launch_ms=round(avg_ms, 4),
                     flops_per_launch=flops_per_launch, achieved=round(achieved, 1), peak=PEAK_BF16_TFLOPS,
                     unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4),

@@ -149,9 +149,11 @@ int tp_dgelu(const void* dy, int64_t ld_dy, const void* preact, int64_t ld_pre,
              void* da, int64_t ld_da, int64_t rows, int64_t cols, void* hip_stream);
 
 /*
- * tp_plan_override -- tuning hook for benchmarks.  key 0: macro-tile id (0 = automatic);
- * key 1: split-K factor (0 = automatic, 1..8); key 2: tile-order group width (0 = automatic).
- * Process-wide; affects later calls.  Returns TP_ERR_MODE for an unknown key or value.
+ * tp_plan_override -- tuning hook for benchmarks and tests.  key 0: macro-tile id (0 = automatic,
+ * 1 = 256x256, 2 = 128x256, 3 = 256x128, 4 = 128x128); key 1: split-K factor (0 = automatic, 1..8);
+ * key 2: tile-order group height in tile rows (0 = automatic, 1..64); key 3: rotate the K-tile
+ * order inside a step from tile to tile (1 = on, the default; 0 = off).  Process-wide; affects
+ * later calls.  Returns TP_ERR_MODE for an unknown key or value.
  */
 int tp_plan_override(int key, int value);
 

@@ -15,7 +15,7 @@ namespace {
 constexpr int kCUs = 256;                       // MI355X compute units
 constexpr int64_t kMaxLd = (int64_t)1 << 21;    // keeps every in-tile byte offset below 2^31
 
-std::atomic<int> g_tile_override{0}, g_split_override{0}, g_group_override{0}, g_dbg{0}, g_variant{0};
+std::atomic<int> g_tile_override{0}, g_split_override{0}, g_group_override{0}, g_rotate{1};
 
 struct Chunks { int rc, kc, cc; };              // row chunks of X/Y, col chunks of X (= row chunks of W), col chunks of W/Y
 
@@ -170,8 +170,8 @@ void fill_common(GemmArgs& a, const Plan& p, int64_t m, int64_t n, int64_t k, in
     std::memset(&a, 0, sizeof(a));
     a.M = (int32_t)m; a.N = (int32_t)n; a.K = (int32_t)k; a.n_steps = n_steps;
     a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.split_k = p.split_k; a.group_m = p.group_m;
-    a.dbg = g_dbg.load();
-    a.variant = g_variant.load();
+    a.max_workgroups = kCUs;
+    a.rotate = g_rotate.load();
 }
 
 }  // namespace
@@ -355,8 +355,7 @@ int tp_plan_override(int key, int value) {
         case 0: if (value < 0 || value > TILE_128x128) return TP_ERR_MODE; g_tile_override = value; return TP_OK;
         case 1: if (value < 0 || value > 8) return TP_ERR_MODE; g_split_override = value; return TP_OK;
         case 2: if (value < 0 || value > 64) return TP_ERR_MODE; g_group_override = value; return TP_OK;
-        case 3: g_dbg = value; return TP_OK;
-        case 4: if (value < 0 || value > 4) return TP_ERR_MODE; g_variant = value; return TP_OK;
+        case 3: g_rotate = value != 0; return TP_OK;
         default: return TP_ERR_MODE;
     }
 }

@@ -33,8 +33,8 @@ struct GemmArgs {
     int32_t gelu;                       // apply erf-GeLU after the bias
     const void* dg; int64_t lddg;       // optional bf16 [M][N]: multiply by GeLU'(dg)
     float* ws;                          // [split_k][M][N] fp32 partials
-    int32_t variant;                    // kernel variant (tuning): bit 0 = two tiles in flight, bit 1 = raised wave priority around MFMAs
-    int32_t dbg;                        // timing experiments only (results become wrong): 1 = fetch only the first tile, 2 = also skip LDS refills, 3 = refetch the first tile every time
+    int32_t rotate;                     // rotate the K-tile order inside a step per C tile
+    int32_t max_workgroups;             // persistent grid size cap (workgroups resident at once)
 };
 
 struct ReduceArgs {

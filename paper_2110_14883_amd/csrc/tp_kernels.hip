@@ -4,19 +4,27 @@
 // products).  bf16 operands, fp32 accumulation in MFMA 32x32x16 tiles.
 //
 // One kernel template serves the three memory forms (NN forward, NT dX, TN dW):
-//   * a workgroup of 8 wave64 (2 along M x 4 along N) owns one BM x BN tile of C and keeps it in
-//     accumulator registers across ALL steps and all K tiles -- no partial C leaves the chip
-//     unless the host asked for a cross-workgroup split of K;
-//   * K tiles of 64 are double-buffered in LDS; the next tile is fetched with 128-bit buffer loads
-//     (out-of-range chunks read as zero, which is how ragged M / K tails are masked) while the
-//     current one feeds the MFMAs;
+//   * persistent workgroups (one per CU) of 8 wave64 walk over the BM x BN tiles of C; a tile's
+//     accumulators stay in registers across ALL steps and all K tiles -- no partial C leaves the
+//     chip unless the host asked for a cross-workgroup split of K;
+//   * ping-pong: waves 0-3 ("P", one per SIMD) stage operand A, waves 4-7 ("Q") stage operand B.
+//     Inside one K tile P multiplies first and refills LDS afterwards, Q refills first and
+//     multiplies afterwards, so every SIMD always has one wave with MFMAs ready while the other
+//     one waits on global loads or writes LDS.  One workgroup barrier per K tile;
+//   * K tiles of 64 are double-buffered in LDS (2 x 64 KB); the tile after next travels through
+//     registers, fetched with 128-bit buffer loads whose out-of-range chunks read as zero (that
+//     is how ragged M / K tails are masked);
 //   * operands whose contraction index is not contiguous in memory are transposed in registers
-//     (byte permutes) on the way into LDS, so the MFMA side always reads 8 consecutive k with one
-//     ds_read_b128;  LDS rows are 128 B with the 16-byte chunk index XOR-swizzled by (row/2)%8;
+//     (8 x 8 blocks, byte permutes) on the way into LDS, so the MFMA side always reads 8
+//     consecutive k with one ds_read_b128; LDS rows are 128 B with the 16-byte chunk index
+//     XOR-swizzled so that fragment reads and both kinds of writes are free of bank conflicts;
 //   * the MFMA is issued with the operands swapped (C^T = B^T A^T) so that each lane ends up with
 //     4 consecutive columns of one row of C: bias / GeLU / GeLU' run in registers and the stores
-//     are 8- or 16-byte wide;
-//   * workgroup ids are spread so that each XCD (own L2) works on a compact patch of tiles.
+//     are 8- or 16-byte wide; the first K tile of the next C tile is already in flight while the
+//     epilogue runs;
+//   * tile ids are spread so that each XCD (own L2) works on a compact patch of tiles.
+#include <type_traits>
+
 #include "tp_internal.h"
 
 namespace tpl {
@@ -117,269 +125,12 @@ __device__ __forceinline__ void epilogue4(const Epilogue& e, float (&v)[4], int 
     }
 }
 
-// byte offset inside one operand tile in LDS: row r (128 B), 16-byte chunk c, swizzled
-__device__ __forceinline__ uint32_t lds_off(int r, int c) {
-    return (uint32_t)(((r << 3) + (c ^ ((r >> 1) & 7))) << 4);
-}
-
 // ---------------------------------------------------------------------------------------------
-// global -> register -> LDS staging of one operand tile (R rows of 64 k each, in LDS)
+// LDS layout and global -> register -> LDS staging of one operand tile (R rows of 64 k in LDS)
 // ---------------------------------------------------------------------------------------------
-// Contraction-contiguous operand: memory [row][k].  Thread t fetches chunk c = t%8 of rows t/8 + 64 i.
-template <int R>
-struct StageKC {
-    static constexpr int NCH = R / 64;
-    u32x4_t reg[NCH];
-
-    __device__ __forceinline__ void load(const uint16_t* ptr, int ld, int rows, int row0, int K, int k0, int t) {
-        const int c = t & 7, r0 = t >> 3;
-        const uint16_t* base = ptr + (int64_t)row0 * ld + k0;
-        const int64_t rem = ((int64_t)(rows - row0 - 1) * ld + (K - k0)) * 2;
-        __amdgpu_buffer_rsrc_t rs = make_rsrc(base, rem);
-        const bool kok = (k0 + c * 8) < K;
-#pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-            const uint32_t off = (uint32_t)(((r0 + 64 * i) * ld + c * 8) * 2);
-            reg[i] = buf_load16(rs, kok ? off : OOB_OFFSET);
-        }
-    }
-    __device__ __forceinline__ void store(char* lds, int t) const {
-        const int c = t & 7, r0 = t >> 3;
-#pragma unroll
-        for (int i = 0; i < NCH; ++i)
-            *reinterpret_cast<u32x4_t*>(lds + lds_off(r0 + 64 * i, c)) = reg[i];
-    }
-};
-
-// Operand stored [k][x] (x = the tile's row index in LDS): each thread fetches KR k-rows of 8 x,
-// transposes them with byte permutes and writes 8 LDS rows of KR consecutive k.
-template <int R>
-struct StageXC {
-    static constexpr int KR = R / 64;          // 4 (R = 256) or 2 (R = 128)
-    static constexpr int XG = R / 64;          // x groups of 64 per tile
-    u32x4_t reg[KR];
-
-    __device__ __forceinline__ void load(const uint16_t* ptr, int ld, int krows, int k0, int X, int x0, int t) {
-        const int l = t & 63, w = t >> 6;
-        const int xg = w % XG, kg = w / XG;
-        const int x = xg * 64 + (l & 7) * 8;
-        const int k = kg * (8 * KR) + (l >> 3) * KR;
-        const uint16_t* base = ptr + (int64_t)k0 * ld + x0;
-        const int64_t rem = ((int64_t)(krows - k0 - 1) * ld + (X - x0)) * 2;
-        __amdgpu_buffer_rsrc_t rs = make_rsrc(base, rem);
-        const bool xok = (x0 + x) < X;
-#pragma unroll
-        for (int i = 0; i < KR; ++i) {
-            const uint32_t off = (uint32_t)(((k + i) * ld + x) * 2);
-            reg[i] = buf_load16(rs, xok ? off : OOB_OFFSET);
-        }
-    }
-    __device__ __forceinline__ void store(char* lds, int t) const {
-        const int l = t & 63, w = t >> 6;
-        const int xg = w % XG, kg = w / XG;
-        const int x = xg * 64 + (l & 7) * 8;
-        const int k = kg * (8 * KR) + (l >> 3) * KR;       // first k of this thread, 0..63
-        const int c = k >> 3;
-        const uint32_t boff = (uint32_t)((k & 7) * 2);
-#pragma unroll
-        for (int wd = 0; wd < 4; ++wd) {
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const uint32_t sel = e ? 0x07060302u : 0x05040100u;
-                const int r = x + 2 * wd + e;
-                char* dst = lds + lds_off(r, c) + boff;
-                if constexpr (KR == 4) {
-                    u32x2_t v = {__builtin_amdgcn_perm(reg[1][wd], reg[0][wd], sel),
-                                 __builtin_amdgcn_perm(reg[3][wd], reg[2][wd], sel)};
-                    *reinterpret_cast<u32x2_t*>(dst) = v;
-                } else {
-                    *reinterpret_cast<uint32_t*>(dst) = __builtin_amdgcn_perm(reg[1][wd], reg[0][wd], sel);
-                }
-            }
-        }
-    }
-};
-
-// workgroup id -> (tile_m, tile_n, split index): consecutive hardware ids go to different XCDs, so
-// give every XCD one contiguous range of the grouped tile order.
-__device__ __forceinline__ void tile_of_block(const GemmArgs& p, int& tm, int& tn, int& z) {
-    const int G = p.tiles_m * p.tiles_n;
-    const int total = G * p.split_k;
-    const int lin = blockIdx.x;
-    const int base = total / N_XCD, rem = total % N_XCD;
-    const int xcd = lin % N_XCD, local = lin / N_XCD;
-    const int v = xcd * base + (xcd < rem ? xcd : rem) + local;
-    z = v / G;
-    const int pid = v - z * G;
-    const int per_group = p.group_m * p.tiles_n;
-    const int g = pid / per_group;
-    const int first_m = g * p.group_m;
-    const int gsz = (p.tiles_m - first_m) < p.group_m ? (p.tiles_m - first_m) : p.group_m;
-    const int in_g = pid - g * per_group;
-    tm = first_m + in_g % gsz;
-    tn = in_g / gsz;
-}
-
-// ---------------------------------------------------------------------------------------------
-// the GEMM kernel
-// ---------------------------------------------------------------------------------------------
-template <int BM, int BN, bool A_KC, bool B_KC, int PF, bool PRIO>
-__global__ __launch_bounds__(NTHREADS) void tp_gemm_kernel(const GemmArgs p) {
-    constexpr int TM = BM / 64;      // 32-row MFMA tiles per wave along M (2 waves along M)
-    constexpr int TN = BN / 128;     // 32-col MFMA tiles per wave along N (4 waves along N)
-    constexpr int A_BYTES = BM * BK * 2;
-    constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
-    extern __shared__ __attribute__((aligned(16))) char lds[];
-
-    const int t = threadIdx.x;
-    const int l = t & 63, w = t >> 6;
-    const int wm = w & 1, wn = w >> 1;
-
-    int tile_m, tile_n, z;
-    tile_of_block(p, tile_m, tile_n, z);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-    const int KT = (p.K + BK - 1) / BK;
-    const int T = p.n_steps * KT;
-    const int Z = p.split_k;
-    const int my_tiles = (T - z + Z - 1) / Z;       // tiles z, z+Z, ... (every step is visited)
-
-    using StageA = typename std::conditional<A_KC, StageKC<BM>, StageXC<BM>>::type;
-    using StageB = typename std::conditional<B_KC, StageKC<BN>, StageXC<BN>>::type;
-    StageA sa[PF];
-    StageB sb[PF];
-
-    auto fetch = [&](int tile, StageA& qa, StageB& qb) {
-        const int s = tile / KT;
-        const int k0 = (tile - s * KT) * BK;
-        const uint16_t* ap = static_cast<const uint16_t*>(p.a[s]);
-        const uint16_t* bp = static_cast<const uint16_t*>(p.b[s]);
-        if constexpr (A_KC) qa.load(ap, p.lda[s], p.M, m0, p.K, k0, t);
-        else                qa.load(ap, p.lda[s], p.K, k0, p.M, m0, t);
-        if constexpr (B_KC) qb.load(bp, p.ldb[s], p.N, n0, p.K, k0, t);
-        else                qb.load(bp, p.ldb[s], p.K, k0, p.N, n0, t);
-    };
-    auto stash = [&](int buf, const StageA& qa, const StageB& qb) {
-        qa.store(lds + buf * STAGE_BYTES, t);
-        qb.store(lds + buf * STAGE_BYTES + A_BYTES, t);
-    };
-
-    f32x16_t acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-    // per-lane fragment addressing: row inside the wave's slab, k chunk = 2 ks + lane/32
-    const int ra = wm * (BM / 2) + (l & 31);
-    const int rb = wn * (BN / 4) + (l & 31);
-    const int ch = l >> 5;
-
-    auto compute = [&](int cur) {
-        const char* la = lds + cur * STAGE_BYTES;
-        const char* lb = la + A_BYTES;
-        if constexpr (PRIO) __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8_t fa[TM], fb[TN];
-#pragma unroll
-            for (int i2 = 0; i2 < TM; ++i2)
-                fa[i2] = *reinterpret_cast<const bf16x8_t*>(la + lds_off(ra + 32 * i2, 2 * ks + ch));
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8_t*>(lb + lds_off(rb + 32 * j, 2 * ks + ch));
-#pragma unroll
-            for (int i2 = 0; i2 < TM; ++i2)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i2][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i2], acc[i2][j], 0, 0, 0);
-        }
-        if constexpr (PRIO) __builtin_amdgcn_s_setprio(0);
-    };
-
-    if constexpr (PF == 1) {
-        // the tile after the current one travels through registers while the current one is multiplied
-        fetch(z, sa[0], sb[0]);
-        stash(0, sa[0], sb[0]);
-        __syncthreads();
-        for (int i = 0; i < my_tiles; ++i) {
-            const int cur = i & 1;
-            const bool more = (i + 1) < my_tiles;
-            if (more && (p.dbg == 0 || p.dbg == 3)) fetch(p.dbg == 3 ? z : z + (i + 1) * Z, sa[0], sb[0]);
-            compute(cur);
-            if (more && p.dbg < 2) stash(cur ^ 1, sa[0], sb[0]);
-            __syncthreads();
-        }
-    } else {
-        // two tiles in flight: tile i+1 waits in one register set (fetched an iteration ago) while
-        // tile i+2 is being fetched into the other
-        fetch(z, sa[0], sb[0]);
-        stash(0, sa[0], sb[0]);
-        if (my_tiles > 1) fetch(z + Z, sa[0], sb[0]);
-        __syncthreads();
-        for (int i = 0; i < my_tiles; i += 2) {
-            // even iteration: LDS buffer 0 is current, set 0 holds tile i+1, set 1 receives tile i+2
-            if (i + 2 < my_tiles) fetch(z + (i + 2) * Z, sa[1], sb[1]);
-            compute(0);
-            if (i + 1 < my_tiles) stash(1, sa[0], sb[0]);
-            __syncthreads();
-            if (i + 1 >= my_tiles) break;
-            // odd iteration: buffer 1 is current, set 1 holds tile i+2, set 0 receives tile i+3
-            if (i + 3 < my_tiles) fetch(z + (i + 3) * Z, sa[0], sb[0]);
-            compute(1);
-            if (i + 2 < my_tiles) stash(0, sa[1], sb[1]);
-            __syncthreads();
-        }
-    }
-
-    // ------------------------------------------------------------------ epilogue
-    // acc[i][j][v]: row m = 32 i + lane%32, columns n = 32 j + 8 (v/4) + 4 (lane/32) + v%4
-    if (Z > 1) {
-        float* wsz = p.ws + (int64_t)z * p.M * p.N;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int m = m0 + wm * (BM / 2) + 32 * i + (l & 31);
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = n0 + wn * (BN / 4) + 32 * j + 8 * g + 4 * ch;
-                    if (m < p.M && n < p.N) {
-                        f32x4_t s = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                        *reinterpret_cast<f32x4_t*>(wsz + (int64_t)m * p.N + n) = s;
-                    }
-                }
-        }
-        return;
-    }
-    Epilogue e{p.out, p.ldo, p.out_f32, p.pre, p.ldp, p.bias, p.gelu, p.dg, p.lddg};
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int m = m0 + wm * (BM / 2) + 32 * i + (l & 31);
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn * (BN / 4) + 32 * j + 8 * g + 4 * ch;
-                if (m < p.M && n < p.N) {
-                    float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                    epilogue4(e, v, m, n);
-                }
-            }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Ping-pong variant.  Waves 0-3 ("P", one per SIMD) stage operand A, waves 4-7 ("Q") stage operand
-// B, each with 256 threads.  Inside one K tile P multiplies first and refills LDS afterwards, Q
-// refills first and multiplies afterwards, so on every SIMD one wave has MFMAs ready while the
-// other one is busy with global loads and LDS writes.  One workgroup barrier per K tile.
-// ---------------------------------------------------------------------------------------------
-// swizzle that keeps both the fragment reads (16 consecutive rows, one chunk) and the transposed
+// byte offset of row r (128 B), 16-byte chunk c.  The swizzle keeps both the fragment reads (16 consecutive rows, one chunk) and the transposed
 // 128-bit writes (rows 8 apart, one chunk) free of bank conflicts
-__device__ __forceinline__ uint32_t lds_off2(int r, int c) {
+__device__ __forceinline__ uint32_t lds_off(int r, int c) {
     return (uint32_t)(((r << 3) + (c ^ (((r >> 1) & 7) ^ ((r >> 4) & 3)))) << 4);
 }
 
@@ -404,7 +155,7 @@ struct HalfKC {
         const int c = tg & 7, r0 = tg >> 3;
 #pragma unroll
         for (int i = 0; i < NCH; ++i)
-            *reinterpret_cast<u32x4_t*>(lds + lds_off2(r0 + 32 * i, c)) = reg[i];
+            *reinterpret_cast<u32x4_t*>(lds + lds_off(r0 + 32 * i, c)) = reg[i];
     }
 };
 
@@ -437,50 +188,88 @@ struct HalfXC {
                 const uint32_t sel = e ? 0x07060302u : 0x05040100u;
                 u32x4_t v = {__builtin_amdgcn_perm(reg[1][wd], reg[0][wd], sel), __builtin_amdgcn_perm(reg[3][wd], reg[2][wd], sel),
                              __builtin_amdgcn_perm(reg[5][wd], reg[4][wd], sel), __builtin_amdgcn_perm(reg[7][wd], reg[6][wd], sel)};
-                *reinterpret_cast<u32x4_t*>(lds + lds_off2(x + 2 * wd + e, c)) = v;
+                *reinterpret_cast<u32x4_t*>(lds + lds_off(x + 2 * wd + e, c)) = v;
             }
         }
     }
 };
 
-template <int BM, int BN, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(NTHREADS) void tp_gemm_pp_kernel(const GemmArgs p) {
-    constexpr int TM = BM / 64;
-    constexpr int TN = BN / 128;
+// virtual tile id -> (tile_m, tile_n, split index).  Workgroup b runs on XCD b % 8 and takes ids b,
+// b + grid, ... (grid is a multiple of 8 whenever there is more than one round), so ids congruent
+// mod 8 stay on one XCD: give every XCD one contiguous range of the grouped tile order.
+__device__ __forceinline__ void tile_of_id(const GemmArgs& p, const int lin, int& tm, int& tn, int& z) {
+    const int G = p.tiles_m * p.tiles_n;
+    const int total = G * p.split_k;
+    const int base = total / N_XCD, rem = total % N_XCD;
+    const int xcd = lin % N_XCD, local = lin / N_XCD;
+    const int v = xcd * base + (xcd < rem ? xcd : rem) + local;
+    z = v / G;
+    const int pid = v - z * G;
+    const int per_group = p.group_m * p.tiles_n;
+    const int g = pid / per_group;
+    const int first_m = g * p.group_m;
+    const int gsz = (p.tiles_m - first_m) < p.group_m ? (p.tiles_m - first_m) : p.group_m;
+    const int in_g = pid - g * per_group;
+    tm = first_m + in_g % gsz;
+    tn = in_g / gsz;
+}
+
+template <int V> using KS = std::integral_constant<int, V>;
+
+struct TileCoord { int m0, n0, z, rot; };
+
+// ---------------------------------------------------------------------------------------------
+// one wave group's part of the GEMM (IS_P: waves 0-3, stage A;  else waves 4-7, stage B)
+// ---------------------------------------------------------------------------------------------
+template <int BM, int BN, bool A_KC, bool B_KC, bool IS_P>
+__device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const int t, const int w) {
+    constexpr int TM = BM / 64;      // 32-row MFMA tiles per wave along M (2 waves along M)
+    constexpr int TN = BN / 128;     // 32-col MFMA tiles per wave along N (4 waves along N)
     constexpr int A_BYTES = BM * BK * 2;
     constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
-    extern __shared__ __attribute__((aligned(16))) char lds[];
+    constexpr int PART = IS_P ? 0 : A_BYTES;          // where this group's operand sits inside a stage
+    using Stage = typename std::conditional<IS_P,
+        typename std::conditional<A_KC, HalfKC<BM>, HalfXC<BM>>::type,
+        typename std::conditional<B_KC, HalfKC<BN>, HalfXC<BN>>::type>::type;
 
-    const int t = threadIdx.x;
-    const int l = t & 63, w = __builtin_amdgcn_readfirstlane(t >> 6);     // wave index, known uniform
-    const int wm = w & 1, wn = ((w >> 1) & 1) | ((w >> 2) << 1);          // P waves: wn in {0,1}; Q waves: wn in {2,3}
-    const bool is_p = w < 4;
-    const int tg = t & 255;
+    const int l = t & 63, tg = t & 255;
+    const int wm = w & 1, wn = ((w >> 1) & 1) | ((w >> 2) << 1);   // P waves: wn in {0,1}; Q waves: wn in {2,3}
+    const int ra = wm * (BM / 2) + (l & 31);       // fragment rows inside the wave's slab
+    const int rb = wn * (BN / 4) + (l & 31);
+    const int ch = l >> 5;                         // k chunk = 2 ks + lane/32
 
-    int tile_m, tile_n, z;
-    tile_of_block(p, tile_m, tile_n, z);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int KT = (p.K + BK - 1) / BK;
     const int T = p.n_steps * KT;
     const int Z = p.split_k;
-    const int my_tiles = (T - z + Z - 1) / Z;
+    const int total = p.tiles_m * p.tiles_n * Z;
 
-    using StageA = typename std::conditional<A_KC, HalfKC<BM>, HalfXC<BM>>::type;
-    using StageB = typename std::conditional<B_KC, HalfKC<BN>, HalfXC<BN>>::type;
+    Stage st;
+    // Inside a step the K tiles are taken in a rotated order that differs from C tile to C tile, so
+    // that the CUs of one XCD are not all asking the same memory channel for the same K offset.
+    auto fetch = [&](const TileCoord& c, int tile) __attribute__((always_inline)) {
+        const int s = tile / KT;
+        int kt = tile - s * KT + c.rot;
+        if (kt >= KT) kt -= KT;
+        const int k0 = kt * BK;
+        if constexpr (IS_P) {
+            const uint16_t* ap = static_cast<const uint16_t*>(p.a[s]);
+            if constexpr (A_KC) st.load(ap, p.lda[s], p.M, c.m0, p.K, k0, tg);
+            else                st.load(ap, p.lda[s], p.K, k0, p.M, c.m0, tg);
+        } else {
+            const uint16_t* bp = static_cast<const uint16_t*>(p.b[s]);
+            if constexpr (B_KC) st.load(bp, p.ldb[s], p.N, c.n0, p.K, k0, tg);
+            else                st.load(bp, p.ldb[s], p.K, k0, p.N, c.n0, tg);
+        }
+    };
+    auto locate = [&](int v) __attribute__((always_inline)) {
+        int tm, tn, z;
+        tile_of_id(p, v, tm, tn, z);
+        const int rot = p.rotate ? ((tm * 3 + tn * 5) & 7) % KT : 0;
+        return TileCoord{tm * BM, tn * BN, z, rot};
+    };
 
     f32x16_t acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-    const int ra = wm * (BM / 2) + (l & 31);
-    const int rb = wn * (BN / 4) + (l & 31);
-    const int ch = l >> 5;
-
-    auto compute = [&](int cur) {
+    auto compute = [&](int cur) __attribute__((always_inline)) {
         const char* la = lds + cur * STAGE_BYTES;
         const char* lb = la + A_BYTES;
         __builtin_amdgcn_s_setprio(1);
@@ -488,96 +277,113 @@ __global__ __launch_bounds__(NTHREADS) void tp_gemm_pp_kernel(const GemmArgs p) 
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8_t fa[TM], fb[TN];
 #pragma unroll
-            for (int i2 = 0; i2 < TM; ++i2)
-                fa[i2] = *reinterpret_cast<const bf16x8_t*>(la + lds_off2(ra + 32 * i2, 2 * ks + ch));
+            for (int i = 0; i < TM; ++i)
+                fa[i] = *reinterpret_cast<const bf16x8_t*>(la + lds_off(ra + 32 * i, 2 * ks + ch));
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8_t*>(lb + lds_off2(rb + 32 * j, 2 * ks + ch));
+                fb[j] = *reinterpret_cast<const bf16x8_t*>(lb + lds_off(rb + 32 * j, 2 * ks + ch));
 #pragma unroll
-            for (int i2 = 0; i2 < TM; ++i2)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i2][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i2], acc[i2][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
         }
         __builtin_amdgcn_s_setprio(0);
     };
 
-    if (is_p) {
-        StageA sa;
-        auto fetch = [&](int tile) {
-            const int s = tile / KT;
-            const int k0 = (tile - s * KT) * BK;
-            const uint16_t* ap = static_cast<const uint16_t*>(p.a[s]);
-            if constexpr (A_KC) sa.load(ap, p.lda[s], p.M, m0, p.K, k0, tg);
-            else                sa.load(ap, p.lda[s], p.K, k0, p.M, m0, tg);
-        };
-        fetch(z);
-        sa.store(lds, tg);
-        if (my_tiles > 1) fetch(z + Z);
-        __syncthreads();
-        for (int i = 0; i < my_tiles; ++i) {
-            const int cur = i & 1;
-            compute(cur);
-            if (i + 1 < my_tiles && p.dbg != 2) sa.store(lds + (cur ^ 1) * STAGE_BYTES, tg);
-            if (i + 2 < my_tiles && (p.dbg == 0 || p.dbg == 3)) fetch(p.dbg == 3 ? z : z + (i + 2) * Z);
-            __syncthreads();
-        }
-    } else {
-        StageB sb;
-        auto fetch = [&](int tile) {
-            const int s = tile / KT;
-            const int k0 = (tile - s * KT) * BK;
-            const uint16_t* bp = static_cast<const uint16_t*>(p.b[s]);
-            if constexpr (B_KC) sb.load(bp, p.ldb[s], p.N, n0, p.K, k0, tg);
-            else                sb.load(bp, p.ldb[s], p.K, k0, p.N, n0, tg);
-        };
-        fetch(z);
-        sb.store(lds + A_BYTES, tg);
-        if (my_tiles > 1) fetch(z + Z);
-        __syncthreads();
-        for (int i = 0; i < my_tiles; ++i) {
-            const int cur = i & 1;
-            if (i + 1 < my_tiles && p.dbg != 2) sb.store(lds + (cur ^ 1) * STAGE_BYTES + A_BYTES, tg);
-            if (i + 2 < my_tiles && (p.dbg == 0 || p.dbg == 3)) fetch(p.dbg == 3 ? z : z + (i + 2) * Z);
-            compute(cur);
-            __syncthreads();
-        }
-    }
+    int v = blockIdx.x;
+    if (v >= total) return;
+    TileCoord cur_tile = locate(v);
+    fetch(cur_tile, cur_tile.z);
 
-    // ------------------------------------------------------------------ epilogue (as in tp_gemm_kernel)
-    if (Z > 1) {
-        float* wsz = p.ws + (int64_t)z * p.M * p.N;
+    while (true) {
+        const int z = cur_tile.z;
+        const int my_tiles = (T - z + Z - 1) / Z;       // K tiles z, z+Z, ...: every step is visited
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int m = m0 + wm * (BM / 2) + 32 * i + (l & 31);
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = n0 + wn * (BN / 4) + 32 * j + 8 * g + 4 * ch;
-                    if (m < p.M && n < p.N) {
-                        f32x4_t s = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                        *reinterpret_cast<f32x4_t*>(wsz + (int64_t)m * p.N + n) = s;
-                    }
-                }
-        }
-        return;
-    }
-    Epilogue e{p.out, p.ldo, p.out_f32, p.pre, p.ldp, p.bias, p.gelu, p.dg, p.lddg};
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int m = m0 + wm * (BM / 2) + 32 * i + (l & 31);
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn * (BN / 4) + 32 * j + 8 * g + 4 * ch;
-                if (m < p.M && n < p.N) {
-                    float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                    epilogue4(e, v, m, n);
-                }
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+        // K tile 0 -> LDS stage 0, K tile 1 -> registers
+        st.store(lds + PART, tg);
+        if (my_tiles > 1) fetch(cur_tile, z + Z);
+        __syncthreads();
+
+        for (int i = 0; i < my_tiles; ++i) {
+            const int cur = i & 1;
+            char* refill = lds + (cur ^ 1) * STAGE_BYTES + PART;    // last read one iteration ago, by everybody
+            if constexpr (IS_P) {
+                compute(cur);
+                if (i + 1 < my_tiles) st.store(refill, tg);
+                if (i + 2 < my_tiles) fetch(cur_tile, z + (i + 2) * Z);
+            } else {
+                if (i + 1 < my_tiles) st.store(refill, tg);
+                if (i + 2 < my_tiles) fetch(cur_tile, z + (i + 2) * Z);
+                compute(cur);
             }
+            __syncthreads();
+        }
+
+        // start on the next C tile's first K tile before the epilogue of this one
+        v += gridDim.x;
+        const bool has_next = v < total;
+        TileCoord next_tile = cur_tile;
+        if (has_next) {
+            next_tile = locate(v);
+            fetch(next_tile, next_tile.z);
+        }
+
+        // ---------------------------------------------------------------- epilogue
+        // acc[i][j][e]: row m = 32 i + lane%32, columns n = 32 j + 8 (e/4) + 4 (lane/32) + e%4
+        const int mrow = cur_tile.m0 + wm * (BM / 2) + (l & 31);
+        const int ncol = cur_tile.n0 + wn * (BN / 4) + 4 * ch;
+        if (Z > 1) {
+            float* wsz = p.ws + (int64_t)z * p.M * p.N;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int m = mrow + 32 * i;
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = ncol + 32 * j + 8 * g;
+                        if (m < p.M && n < p.N) {
+                            f32x4_t s = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                            *reinterpret_cast<f32x4_t*>(wsz + (int64_t)m * p.N + n) = s;
+                        }
+                    }
+            }
+        } else {
+            Epilogue e{p.out, p.ldo, p.out_f32, p.pre, p.ldp, p.bias, p.gelu, p.dg, p.lddg};
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int m = mrow + 32 * i;
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = ncol + 32 * j + 8 * g;
+                        if (m < p.M && n < p.N) {
+                            float x[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                            epilogue4(e, x, m, n);
+                        }
+                    }
+            }
+        }
+        if (!has_next) break;
+        cur_tile = next_tile;
     }
+}
+
+template <int BM, int BN, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(NTHREADS) void tp_gemm_kernel(const GemmArgs p) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int t = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(t >> 6);     // wave index, known uniform
+    if (w < 4) gemm_role<BM, BN, A_KC, B_KC, true>(p, lds, t, w);
+    else       gemm_role<BM, BN, A_KC, B_KC, false>(p, lds, t, w);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -661,56 +467,30 @@ void tile_shape(int tile_id, int* bm, int* bn) {
     }
 }
 
-template <int BM, int BN, bool A_KC, bool B_KC, int PF, bool PRIO>
+template <int BM, int BN, bool A_KC, bool B_KC>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
     constexpr int lds_bytes = 2 * (BM + BN) * BK * 2;
     static bool attr_set = false;           // same value every time: a repeated set is harmless
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tp_gemm_kernel<BM, BN, A_KC, B_KC, PF, PRIO>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tp_gemm_kernel<BM, BN, A_KC, B_KC>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const unsigned grid = (unsigned)(a.tiles_m * a.tiles_n * a.split_k);
-    hipLaunchKernelGGL((tp_gemm_kernel<BM, BN, A_KC, B_KC, PF, PRIO>), dim3(grid), dim3(NTHREADS), lds_bytes, stream, a);
-    return hipGetLastError();
-}
-
-template <int BM, int BN, bool A_KC, bool B_KC>
-static hipError_t launch_pp(const GemmArgs& a, hipStream_t stream) {
-    constexpr int lds_bytes = 2 * (BM + BN) * BK * 2;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tp_gemm_pp_kernel<BM, BN, A_KC, B_KC>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    const unsigned grid = (unsigned)(a.tiles_m * a.tiles_n * a.split_k);
-    hipLaunchKernelGGL((tp_gemm_pp_kernel<BM, BN, A_KC, B_KC>), dim3(grid), dim3(NTHREADS), lds_bytes, stream, a);
+    // persistent: never more workgroups than the chip holds at once (one per CU with this much LDS)
+    const int total = a.tiles_m * a.tiles_n * a.split_k;
+    const unsigned grid = (unsigned)(total < a.max_workgroups ? total : a.max_workgroups);
+    hipLaunchKernelGGL((tp_gemm_kernel<BM, BN, A_KC, B_KC>), dim3(grid), dim3(NTHREADS), lds_bytes, stream, a);
     return hipGetLastError();
 }
 
 template <bool A_KC, bool B_KC>
 static hipError_t launch_form(int tile_id, const GemmArgs& a, hipStream_t s) {
-    if (a.variant == 0) {
-        switch (tile_id) {
-            case TILE_256x256: return launch_pp<256, 256, A_KC, B_KC>(a, s);
-            case TILE_128x256: return launch_pp<128, 256, A_KC, B_KC>(a, s);
-            case TILE_256x128: return launch_pp<256, 128, A_KC, B_KC>(a, s);
-            case TILE_128x128: return launch_pp<128, 128, A_KC, B_KC>(a, s);
-            default: return hipErrorInvalidValue;
-        }
-    }
     switch (tile_id) {
-        case TILE_256x256:
-            switch (a.variant) {
-                case 2: return launch_one<256, 256, A_KC, B_KC, 1, true>(a, s);
-                default: return launch_one<256, 256, A_KC, B_KC, 1, false>(a, s);
-            }
-        case TILE_128x256: return launch_one<128, 256, A_KC, B_KC, 1, false>(a, s);
-        case TILE_256x128: return launch_one<256, 128, A_KC, B_KC, 1, false>(a, s);
-        case TILE_128x128: return launch_one<128, 128, A_KC, B_KC, 1, false>(a, s);
+        case TILE_256x256: return launch_one<256, 256, A_KC, B_KC>(a, s);
+        case TILE_128x256: return launch_one<128, 256, A_KC, B_KC>(a, s);
+        case TILE_256x128: return launch_one<256, 128, A_KC, B_KC>(a, s);
+        case TILE_128x128: return launch_one<128, 128, A_KC, B_KC>(a, s);
         default: return hipErrorInvalidValue;
     }
 }
