@@ -42,6 +42,8 @@ constexpr int NTHREADS = 512;       // 8 waves
 constexpr uint32_t OOB_OFFSET = 0x80000000u;   // >= every num_records we ever set
 constexpr uint32_t MAX_RECORDS = 0x80000000u;
 constexpr int N_XCD = 8;
+enum { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_GELU = 2, EPI_MUL_DGELU = 3 };   // epilogue kinds compiled into the GEMM
+constexpr int EPI_BYTES_PER_WAVE = 4096;      // epilogue staging patch: 32 rows x 128 bytes per wave
 
 // ---------------------------------------------------------------------------------------------
 // small device helpers
@@ -221,7 +223,7 @@ struct TileCoord { int m0, n0, z, rot; };
 // ---------------------------------------------------------------------------------------------
 // one wave group's part of the GEMM (IS_P: waves 0-3, stage A;  else waves 4-7, stage B)
 // ---------------------------------------------------------------------------------------------
-template <int BM, int BN, bool A_KC, bool B_KC, bool IS_P>
+template <int BM, int BN, bool A_KC, bool B_KC, int EPI, bool F32_OUT, bool IS_P>
 __device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const int t, const int w) {
     constexpr int TM = BM / 64;      // 32-row MFMA tiles per wave along M (2 waves along M)
     constexpr int TN = BN / 128;     // 32-col MFMA tiles per wave along N (4 waves along N)
@@ -237,6 +239,7 @@ __device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const in
     const int ra = wm * (BM / 2) + (l & 31);       // fragment rows inside the wave's slab
     const int rb = wn * (BN / 4) + (l & 31);
     const int ch = l >> 5;                         // k chunk = 2 ks + lane/32
+    char* const eps = lds + 2 * STAGE_BYTES + w * EPI_BYTES_PER_WAVE;   // wave-private epilogue patch
 
     const int KT = (p.K + BK - 1) / BK;
     const int T = p.n_steps * KT;
@@ -269,24 +272,42 @@ __device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const in
     };
 
     f32x16_t acc[TM][TN];
+    // One K tile = 4 MFMA k-steps.  The fragment reads of step ks+1 are issued while the MFMAs of
+    // step ks run: the B fragments are double-buffered, an A fragment's registers are re-read as
+    // soon as its two MFMAs have issued.  The sched_group_barrier calls pin that interleaving
+    // (2 MFMA, 1 LDS read, ...), so a wave that multiplies alone still keeps the MFMA pipe busy.
     auto compute = [&](int cur) __attribute__((always_inline)) {
         const char* la = lds + cur * STAGE_BYTES;
         const char* lb = la + A_BYTES;
+        bf16x8_t fa[TM], fb[2][TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            fb[0][j] = *reinterpret_cast<const bf16x8_t*>(lb + lds_off(rb + 32 * j, ch));
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            fa[i] = *reinterpret_cast<const bf16x8_t*>(la + lds_off(ra + 32 * i, ch));
+        __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
         __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8_t fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                fa[i] = *reinterpret_cast<const bf16x8_t*>(la + lds_off(ra + 32 * i, 2 * ks + ch));
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8_t*>(lb + lds_off(rb + 32 * j, 2 * ks + ch));
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
+            const bool more = ks + 1 < BK / 16;
+            if (more) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+                    fb[(ks + 1) & 1][j] = *reinterpret_cast<const bf16x8_t*>(lb + lds_off(rb + 32 * j, 2 * (ks + 1) + ch));
+                __builtin_amdgcn_sched_group_barrier(0x100, TN, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks & 1][j], fa[i], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, TN, 0);
+                if (more) {
+                    fa[i] = *reinterpret_cast<const bf16x8_t*>(la + lds_off(ra + 32 * i, 2 * (ks + 1) + ch));
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+            }
         }
         __builtin_amdgcn_s_setprio(0);
     };
@@ -326,64 +347,121 @@ __device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const in
             __syncthreads();
         }
 
-        // start on the next C tile's first K tile before the epilogue of this one
-        v += gridDim.x;
-        const bool has_next = v < total;
-        TileCoord next_tile = cur_tile;
-        if (has_next) {
-            next_tile = locate(v);
-            fetch(next_tile, next_tile.z);
-        }
 
         // ---------------------------------------------------------------- epilogue
-        // acc[i][j][e]: row m = 32 i + lane%32, columns n = 32 j + 8 (e/4) + 4 (lane/32) + e%4
-        const int mrow = cur_tile.m0 + wm * (BM / 2) + (l & 31);
-        const int ncol = cur_tile.n0 + wn * (BN / 4) + 4 * ch;
-        if (Z > 1) {
-            float* wsz = p.ws + (int64_t)z * p.M * p.N;
+        // acc[i][j][e]: row m = 32 i + lane%32, columns n = 32 j + 8 (e/4) + 4 (lane/32) + e%4.
+        // Bias / GeLU / GeLU' are applied in registers; every 32-row slab then passes through a
+        // wave-private 4 KB LDS patch so that the global stores are whole 128-byte row segments.
+        {
+            const int m_sub = cur_tile.m0 + wm * (BM / 2);          // first row of this wave's slab
+            const int n_sub = cur_tile.n0 + wn * (BN / 4);          // first column
+            const int r = l & 31;                                   // row of this lane inside a 32-row slab
+            const bool partial = Z > 1;          // split K: raw fp32 partials, the fix-up kernel runs the epilogue
+            constexpr bool use_bias = EPI == EPI_BIAS || EPI == EPI_BIAS_GELU;
+            constexpr bool use_gelu = EPI == EPI_BIAS_GELU;
+            constexpr bool use_dg = EPI == EPI_MUL_DGELU;
+            const bool use_pre = !use_dg && p.pre != nullptr;
+
+            // value functors: 4 consecutive columns (j, g) of row r of slab i
+            auto raw4 = [&](int i, int j, int g, float (&v)[4]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int m = mrow + 32 * i;
+                for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * g + e];
+            };
+            auto preact4 = [&](int i, int j, int g, float (&v)[4]) __attribute__((always_inline)) {
+                raw4(i, j, g, v);
+                if constexpr (use_bias) {
+                    const int n = n_sub + 32 * j + 8 * g + 4 * ch;
+                    u32x2_t b = {0u, 0u};
+                    if (n < p.N) b = *reinterpret_cast<const u32x2_t*>(static_cast<const uint16_t*>(p.bias) + n);
+                    v[0] += bf16_lo(b[0]); v[1] += bf16_hi(b[0]); v[2] += bf16_lo(b[1]); v[3] += bf16_hi(b[1]);
+                }
+            };
+            auto final4 = [&](int i, int j, int g, float (&v)[4]) __attribute__((always_inline)) {
+                preact4(i, j, g, v);
+                if constexpr (use_gelu) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = gelu_f(v[e]);
+                }
+                if constexpr (use_dg) {
+                    const int m = m_sub + 32 * i + r, n = n_sub + 32 * j + 8 * g + 4 * ch;
+                    if (m < p.M && n < p.N) {
+                        const u32x2_t a = *reinterpret_cast<const u32x2_t*>(static_cast<const uint16_t*>(p.dg) + (int64_t)m * p.lddg + n);
+                        v[0] *= dgelu_f(bf16_lo(a[0])); v[1] *= dgelu_f(bf16_hi(a[0]));
+                        v[2] *= dgelu_f(bf16_lo(a[1])); v[3] *= dgelu_f(bf16_hi(a[1]));
+                    }
+                }
+            };
+            // bf16 slab: rows of 32*TN bf16 (RB bytes); lane writes 8 bytes, reads back 16
+            constexpr int RB = 32 * TN * 2, CPR = RB / 16, RPI = 64 / CPR;      // chunks per row, rows per instruction
+            auto sw16 = [](int row) { return (row / (256 / RB)) & (CPR - 1); };
+            auto slab_bf16 = [&](int i, auto value4, uint16_t* base, int64_t ld) __attribute__((always_inline)) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
-                        const int n = ncol + 32 * j + 8 * g;
-                        if (m < p.M && n < p.N) {
-                            f32x4_t s = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                            *reinterpret_cast<f32x4_t*>(wsz + (int64_t)m * p.N + n) = s;
-                        }
+                        float x[4];
+                        value4(i, j, g, x);
+                        const u32x2_t v = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3])};
+                        *reinterpret_cast<u32x2_t*>(eps + r * RB + (((4 * j + g) ^ sw16(r)) << 4) + 8 * ch) = v;
                     }
-            }
-        } else {
-            Epilogue e{p.out, p.ldo, p.out_f32, p.pre, p.ldp, p.bias, p.gelu, p.dg, p.lddg};
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int m = mrow + 32 * i;
+                for (int it = 0; it < 32 / RPI; ++it) {
+                    const int rr = it * RPI + l / CPR, c = l % CPR;
+                    const u32x4_t v = *reinterpret_cast<const u32x4_t*>(eps + rr * RB + ((c ^ sw16(rr)) << 4));
+                    const int m = m_sub + 32 * i + rr, n = n_sub + 8 * c;
+                    if (m < p.M && n < p.N) *reinterpret_cast<u32x4_t*>(base + (int64_t)m * ld + n) = v;
+                }
+            };
+            // fp32 slab, one 32-column block at a time: rows of 128 bytes; lane writes 16 bytes, reads back 16
+            auto slab_f32 = [&](int i, auto value4, float* base, int64_t ld) __attribute__((always_inline)) {
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < TN; ++j) {
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
-                        const int n = ncol + 32 * j + 8 * g;
-                        if (m < p.M && n < p.N) {
-                            float x[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                            epilogue4(e, x, m, n);
-                        }
+                        float x[4];
+                        value4(i, j, g, x);
+                        const f32x4_t v = {x[0], x[1], x[2], x[3]};
+                        *reinterpret_cast<f32x4_t*>(eps + r * 128 + (((2 * g + ch) ^ ((r >> 1) & 7)) << 4)) = v;
                     }
+#pragma unroll
+                    for (int it = 0; it < 4; ++it) {
+                        const int rr = it * 8 + (l >> 3), c = l & 7;
+                        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(eps + rr * 128 + ((c ^ ((rr >> 1) & 7)) << 4));
+                        const int m = m_sub + 32 * i + rr, n = n_sub + 32 * j + 4 * c;
+                        if (m < p.M && n < p.N) *reinterpret_cast<f32x4_t*>(base + (int64_t)m * ld + n) = v;
+                    }
+                }
+            };
+
+            if (partial) {
+                float* const wsz = p.ws + (int64_t)z * p.M * p.N;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) slab_f32(i, raw4, wsz, (int64_t)p.N);
+            } else {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    if constexpr (!use_dg) {
+                        if (use_pre) slab_bf16(i, preact4, static_cast<uint16_t*>(p.pre), p.ldp);
+                    }
+                    if constexpr (F32_OUT) slab_f32(i, final4, static_cast<float*>(p.out), p.ldo);
+                    else                   slab_bf16(i, final4, static_cast<uint16_t*>(p.out), p.ldo);
+                }
             }
         }
-        if (!has_next) break;
-        cur_tile = next_tile;
+        v += gridDim.x;
+        if (v >= total) break;
+        cur_tile = locate(v);
+        fetch(cur_tile, cur_tile.z);
     }
 }
 
-template <int BM, int BN, bool A_KC, bool B_KC>
+template <int BM, int BN, bool A_KC, bool B_KC, int EPI, bool F32_OUT>
 __global__ __launch_bounds__(NTHREADS) void tp_gemm_kernel(const GemmArgs p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int t = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(t >> 6);     // wave index, known uniform
-    if (w < 4) gemm_role<BM, BN, A_KC, B_KC, true>(p, lds, t, w);
-    else       gemm_role<BM, BN, A_KC, B_KC, false>(p, lds, t, w);
+    if (w < 4) gemm_role<BM, BN, A_KC, B_KC, EPI, F32_OUT, true>(p, lds, t, w);
+    else       gemm_role<BM, BN, A_KC, B_KC, EPI, F32_OUT, false>(p, lds, t, w);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -467,12 +545,12 @@ void tile_shape(int tile_id, int* bm, int* bn) {
     }
 }
 
-template <int BM, int BN, bool A_KC, bool B_KC>
+template <int BM, int BN, bool A_KC, bool B_KC, int EPI, bool F32_OUT>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
-    constexpr int lds_bytes = 2 * (BM + BN) * BK * 2;
+    constexpr int lds_bytes = 2 * (BM + BN) * BK * 2 + 8 * EPI_BYTES_PER_WAVE;
     static bool attr_set = false;           // same value every time: a repeated set is harmless
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tp_gemm_kernel<BM, BN, A_KC, B_KC>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tp_gemm_kernel<BM, BN, A_KC, B_KC, EPI, F32_OUT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -480,26 +558,39 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
     // persistent: never more workgroups than the chip holds at once (one per CU with this much LDS)
     const int total = a.tiles_m * a.tiles_n * a.split_k;
     const unsigned grid = (unsigned)(total < a.max_workgroups ? total : a.max_workgroups);
-    hipLaunchKernelGGL((tp_gemm_kernel<BM, BN, A_KC, B_KC>), dim3(grid), dim3(NTHREADS), lds_bytes, stream, a);
+    hipLaunchKernelGGL((tp_gemm_kernel<BM, BN, A_KC, B_KC, EPI, F32_OUT>), dim3(grid), dim3(NTHREADS), lds_bytes, stream, a);
     return hipGetLastError();
 }
 
-template <bool A_KC, bool B_KC>
-static hipError_t launch_form(int tile_id, const GemmArgs& a, hipStream_t s) {
-    switch (tile_id) {
-        case TILE_256x256: return launch_one<256, 256, A_KC, B_KC>(a, s);
-        case TILE_128x256: return launch_one<128, 256, A_KC, B_KC>(a, s);
-        case TILE_256x128: return launch_one<256, 128, A_KC, B_KC>(a, s);
-        case TILE_128x128: return launch_one<128, 128, A_KC, B_KC>(a, s);
+template <int BM, int BN>
+static hipError_t launch_tile(int form, const GemmArgs& a, hipStream_t s) {
+    // the epilogue is compiled in, per memory form: forward (NN) adds bias / GeLU, dX (NT) may
+    // multiply by GeLU', dW (TN) stores plain fp32.  A launch that splits K writes raw partials.
+    const int epi = a.split_k > 1 ? EPI_NONE : (a.dg ? EPI_MUL_DGELU : (a.gelu ? EPI_BIAS_GELU : (a.bias ? EPI_BIAS : EPI_NONE)));
+    const bool f32 = a.split_k > 1 || a.out_f32;
+    switch (form) {
+        case FORM_NN:
+            if (epi == EPI_BIAS_GELU) return f32 ? launch_one<BM, BN, true, false, EPI_BIAS_GELU, true>(a, s) : launch_one<BM, BN, true, false, EPI_BIAS_GELU, false>(a, s);
+            if (epi == EPI_BIAS)      return f32 ? launch_one<BM, BN, true, false, EPI_BIAS, true>(a, s) : launch_one<BM, BN, true, false, EPI_BIAS, false>(a, s);
+            if (epi == EPI_NONE)      return f32 ? launch_one<BM, BN, true, false, EPI_NONE, true>(a, s) : launch_one<BM, BN, true, false, EPI_NONE, false>(a, s);
+            return hipErrorInvalidValue;
+        case FORM_NT:
+            if (epi == EPI_MUL_DGELU) return f32 ? launch_one<BM, BN, true, true, EPI_MUL_DGELU, true>(a, s) : launch_one<BM, BN, true, true, EPI_MUL_DGELU, false>(a, s);
+            if (epi == EPI_NONE)      return f32 ? launch_one<BM, BN, true, true, EPI_NONE, true>(a, s) : launch_one<BM, BN, true, true, EPI_NONE, false>(a, s);
+            return hipErrorInvalidValue;
+        case FORM_TN:
+            if (epi == EPI_NONE && f32) return launch_one<BM, BN, false, false, EPI_NONE, true>(a, s);
+            return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
 }
 
 hipError_t launch_gemm(int form, int tile_id, const GemmArgs& a, hipStream_t s) {
-    switch (form) {
-        case FORM_NN: return launch_form<true, false>(tile_id, a, s);
-        case FORM_NT: return launch_form<true, true>(tile_id, a, s);
-        case FORM_TN: return launch_form<false, false>(tile_id, a, s);
+    switch (tile_id) {
+        case TILE_256x256: return launch_tile<256, 256>(form, a, s);
+        case TILE_128x256: return launch_tile<128, 256>(form, a, s);
+        case TILE_256x128: return launch_tile<256, 128>(form, a, s);
+        case TILE_128x128: return launch_tile<128, 128>(form, a, s);
         default: return hipErrorInvalidValue;
     }
 }
