@@ -33,14 +33,23 @@ NSETS = 3                          # buffer sets rotated through, so nothing is 
 # HBM-side bytes per launch (read + written) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/gemm_256x256_config2_1d_mlp.md (scaled there by a copy of known size).
 MEASURED_TRAFFIC_BYTES = {
-    "tpl::tp_gemm_kernel<256, 256, true, false>": 1338467739,
-    "tpl::tp_gemm_kernel<256, 256, true, true>": 1305676211,
-    "tpl::tp_gemm_kernel<256, 256, false, false>": 897679149,
+    "tpl::tp_gemm_kernel<256, 256, true, false, 2, false>": 1175168167,
+    "tpl::tp_gemm_kernel<256, 256, true, false, 0, true>": 1163485924,
+    "tpl::tp_gemm_kernel<256, 256, true, true, 3, false>": 1236987189,
+    "tpl::tp_gemm_kernel<256, 256, true, true, 0, true>": 1191737286,
+    "tpl::tp_gemm_kernel<256, 256, false, false, 0, true>": 897861458,
 }
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def gemm_symbol(form: str, epi: int, f32_out: bool) -> str:
+    """Name of the 256x256 GEMM instantiation a call launches (as rocprofv3 prints it, without
+    'void' and the argument list).  form: NN / NT / TN; epi: 0 none, 1 bias, 2 bias+GeLU, 3 *GeLU'."""
+    kc = {"NN": "true, false", "NT": "true, true", "TN": "false, false"}[form]
+    return f"tpl::tp_gemm_kernel<256, 256, {kc}, {epi}, {'true' if f32_out else 'false'}>"
 
 
 def main() -> int:
@@ -98,18 +107,18 @@ def main() -> int:
                      dW2=empty((fb, H), True), dX=empty((M, H), True), dW1=empty((H, fb), True),
                      ws1=ws_for(g1, d1), ws2=ws_for(g2, d2))
             calls = [
-                ("fc1_fwd NN +bias+GeLU", one, lambda b=b, o=o: T.tp_linear_fwd(
+                ("fc1_fwd NN +bias+GeLU", one, gemm_symbol("NN", 2, False), lambda b=b, o=o: T.tp_linear_fwd(
                     g1, d1, 1, [b["X"]], [b["W1"]], b["b1"], T.EPI_BIAS_GELU, o["Z"], o["A"], o["ws1"])),
-                ("fc2_fwd NN fp32 partial", one, lambda b=b, o=o: T.tp_linear_fwd(
+                ("fc2_fwd NN fp32 partial", one, gemm_symbol("NN", 0, True), lambda b=b, o=o: T.tp_linear_fwd(
                     g2, d2, 1, [o["Z"]], [b["W2"]], None, T.EPI_NONE, o["Y"], None, o["ws2"])),
-                ("fc2_dX NT *GeLU'", one, lambda b=b, o=o: T.tp_linear_bwd(
+                ("fc2_dX NT *GeLU'", one, gemm_symbol("NT", 3, False), lambda b=b, o=o: T.tp_linear_bwd(
                     g2, d2, 1, 0, da_row_blocks=[b["G"]], w_blocks_dx=[b["W2"]], dgelu_preact=o["A"], dx=o["dA"],
                     workspace=o["ws2"])),
-                ("fc2_dW TN", one, lambda b=b, o=o: T.tp_linear_bwd(
+                ("fc2_dW TN", one, gemm_symbol("TN", 0, True), lambda b=b, o=o: T.tp_linear_bwd(
                     g2, d2, 0, 1, x_blocks_dw=[o["Z"]], da_col_blocks=[b["G"]], dw=o["dW2"], workspace=o["ws2"])),
-                ("fc1_dX NT fp32 partial", one, lambda b=b, o=o: T.tp_linear_bwd(
+                ("fc1_dX NT fp32 partial", one, gemm_symbol("NT", 0, True), lambda b=b, o=o: T.tp_linear_bwd(
                     g1, d1, 1, 0, da_row_blocks=[o["dA"]], w_blocks_dx=[b["W1"]], dx=o["dX"], workspace=o["ws1"])),
-                ("fc1_dW TN", one, lambda b=b, o=o: T.tp_linear_bwd(
+                ("fc1_dW TN", one, gemm_symbol("TN", 0, True), lambda b=b, o=o: T.tp_linear_bwd(
                     g1, d1, 0, 1, x_blocks_dw=[b["X"]], da_col_blocks=[o["dA"]], dw=o["dW1"], workspace=o["ws1"])),
             ]
             sets.append(calls)
@@ -153,18 +162,18 @@ def main() -> int:
                 return v.clone()
             b = {k_: cp(v) for k_, v in base.items()}
             o = dict(y=empty((m, n), f32y), pre=empty((m, n)), ws=ws_for(grid, dims))
-            calls = [("fwd NN +bias+GeLU", one, lambda b=b, o=o: T.tp_linear_fwd(
+            calls = [("fwd NN +bias+GeLU", one, gemm_symbol("NN", 2, f32y), lambda b=b, o=o: T.tp_linear_fwd(
                 grid, dims, sf, b["x"], b["w"], b["bias"], T.EPI_BIAS_GELU, o["y"], o["pre"], o["ws"]))]
             if cfg.backward:
                 o.update(da=empty((m, n)), dx=empty((m, k), cfg.dx_dtype == "f32"), dw=empty((k, n), True))
                 rows = [o["da"] if i == inp["own_slot_dx"] else b["da_row"][i] for i in range(sx)]
                 cols = [o["da"] if i == inp["own_slot_dw"] else b["da_col"][i] for i in range(sw)]
                 calls += [
-                    ("dA = dY*GeLU'(A)", 0.0, lambda b=b, o=o: T.tp_linear_bwd(
+                    ("dA = dY*GeLU'(A)", 0.0, "tpl::tp_dgelu_kernel", lambda b=b, o=o: T.tp_linear_bwd(
                         grid, dims, 0, 0, dy_own=b["g"], preact_own=o["pre"], da_own_out=o["da"], workspace=o["ws"])),
-                    ("dX NT", one, lambda b=b, o=o, rows=rows: T.tp_linear_bwd(
+                    ("dX NT", one, gemm_symbol("NT", 0, cfg.dx_dtype == "f32"), lambda b=b, o=o, rows=rows: T.tp_linear_bwd(
                         grid, dims, sx, 0, da_row_blocks=rows, w_blocks_dx=b["wdx"], dx=o["dx"], workspace=o["ws"])),
-                    ("dW TN", one, lambda b=b, o=o, cols=cols: T.tp_linear_bwd(
+                    ("dW TN", one, gemm_symbol("TN", 0, True), lambda b=b, o=o, cols=cols: T.tp_linear_bwd(
                         grid, dims, 0, sw, x_blocks_dw=b["xdw"], da_col_blocks=cols, dw=o["dw"], workspace=o["ws"])),
                 ]
             sets.append(calls)
@@ -177,7 +186,7 @@ def main() -> int:
         log(f"[bench] {cfg.name}: inputs ready in {time.time() - t0:.1f}s; warmup {warmup}, steps {steps}")
         ncall = len(sets[0])
         for i in range(warmup):
-            for _, _, fn in sets[i % NSETS]:
+            for _, _, _, fn in sets[i % NSETS]:
                 fn()
         torch.cuda.synchronize()
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(ncall + 1)] for _ in range(steps)]
@@ -186,16 +195,17 @@ def main() -> int:
         for i in range(steps):
             calls = sets[i % NSETS]
             ev[i][0].record(stream)
-            for j, (_, _, fn) in enumerate(calls):
+            for j, (_, _, _, fn) in enumerate(calls):
                 fn()
                 ev[i][j + 1].record(stream)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         ms_step = wall * 1e3 / steps
         per_call = []
-        for j, (label, fl, _) in enumerate(sets[0]):
+        for j, (label, fl, sym, _) in enumerate(sets[0]):
             ms = sum(ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(steps)) / steps
-            per_call.append(dict(call=label, ms=round(ms, 4), tflops=round(fl / ms / 1e9, 1) if fl else None))
+            per_call.append(dict(call=label, kernel=sym, ms=round(ms, 4), flops=fl,
+                                 tflops=round(fl / ms / 1e9, 1) if fl else None))
         res = dict(workload=cfg.name, note=cfg.note, ms_per_step=round(ms_step, 4), gemm_flops=flops,
                    tflops=round(flops / ms_step / 1e9, 1), pct_of_peak=round(flops / ms_step / 1e9 / PEAK_BF16_TFLOPS * 100, 2),
                    calls=per_call)
@@ -206,19 +216,15 @@ def main() -> int:
     cfg = WL.config(args.config)
     main_res = run_config(cfg, args.steps, args.warmup)
 
-    # dominant kernel = the GEMM form with the largest share of the step
-    by_form = {}
+    # dominant kernel = the kernel symbol with the largest share of the step
+    by_sym = {}
     for c in main_res["calls"]:
-        if c["tflops"] is None:
-            continue
-        form = c["call"].split()[1]
-        by_form.setdefault(form, []).append(c)
-    form, lst = max(by_form.items(), key=lambda kv: sum(c["ms"] for c in kv[1]))
-    flops_per_launch = main_res["gemm_flops"] / sum(len(v) for v in by_form.values())
+        if c["tflops"] is not None:
+            by_sym.setdefault(c["kernel"], []).append(c)
+    kname, lst = max(by_sym.items(), key=lambda kv: sum(c["ms"] for c in kv[1]))
+    flops_per_launch = sum(c["flops"] for c in lst) / len(lst)
     avg_ms = sum(c["ms"] for c in lst) / len(lst)
     achieved = flops_per_launch / avg_ms / 1e9
-    kname = {"NN": "tpl::tp_gemm_kernel<256, 256, true, false>", "NT": "tpl::tp_gemm_kernel<256, 256, true, true>",
-             "TN": "tpl::tp_gemm_kernel<256, 256, false, false>"}[form]
     roofline = dict(bound="mfma", kernel=kname, launches_per_step=len(lst), avg_launch_ms=round(avg_ms, 4),
                     flops_per_launch=flops_per_launch, achieved=round(achieved, 1), peak=PEAK_BF16_TFLOPS,
                     unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4),

@@ -104,15 +104,17 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int n_steps) {
         tile_shape(tile_ids[ti], &bm, &bn);
         const int64_t tm = (m + bm - 1) / bm, tn = (n + bn - 1) / bn;
         const int64_t tiles = tm * tn;
-        // cycles one workgroup spends on one 64-deep K tile at ~60 % MFMA rate; smaller tiles move
-        // more LDS bytes per flop and are charged for it
-        const double penalty = (bm == 256 && bn == 256) ? 1.0 : (bm == 128 && bn == 128 ? 1.35 : 1.12);
+        // cycles one workgroup spends on one 64-deep K tile (measured: ~1.8 us at ~1.8 GHz for
+        // 256x256); half and quarter tiles move more bytes per flop and measure ~1.3x / ~1.65x
+        // slower per flop; every C tile also costs a fixed ~11 us (epilogue, pipeline refill)
+        const double penalty = (bm == 256 && bn == 256) ? 1.0 : (bm == 128 && bn == 128 ? 1.65 : 1.3);
         const double tile_cycles = (double)bm * bn * 64 * 2 / 4096.0 / 0.6 * penalty;
+        const double per_tile = 20000.0;
         for (int z = 1; z <= 8; ++z) {
             if (forced_split && z != forced_split) continue;
             if (z > T) break;
             const int64_t waves = (tiles * z + kCUs - 1) / kCUs;
-            const double main_cost = (double)waves * (double)((T + z - 1) / z) * tile_cycles;
+            const double main_cost = (double)waves * ((double)((T + z - 1) / z) * tile_cycles + per_tile);
             // partials: z fp32 planes written and read back at ~1.6 KB/clk, plus one more launch
             const double fix = z > 1 ? (double)m * n * 8.0 * z / 1667.0 + 12000.0 : 0.0;
             const double cost = main_cost + fix;

@@ -136,6 +136,8 @@ def test_argument_errors_before_any_launch():
     assert _st(lambda: T.tp_dgelu((0x10000, 0), (0x10000, 0), (0x10000, 0), 4, 12, stream=0)) in (4, 5)
     assert _st(lambda: T.tp_plan_override(9, 0)) == 2
     assert _st(lambda: T.tp_plan_override(1, 99)) == 2
+    assert _st(lambda: T.tp_plan_override(0, 5)) == 2
+    T.tp_plan_override(3, 1)
 
 
 def test_workspace_size_bounds():
