@@ -28,7 +28,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0          # MI355X dense bf16 MFMA peak (published figure, 2.5 PFLOP/s)
-NSETS = 3                          # buffer sets rotated through, so nothing is re-served from the 256 MB MALL
+NSETS = int(os.environ.get("TPL_BENCH_NSETS", "3"))   # buffer sets rotated through, so nothing is re-served from the 256 MB MALL
 
 # HBM-side bytes per launch (read + written) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/gemm_256x256_config2_1d_mlp.md (scaled there by a copy of known size).
@@ -60,7 +60,7 @@ def main() -> int:
     ap.add_argument("--config", default="c2_1d_n4_mlp")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--extra-steps", type=int, default=10)
+    ap.add_argument("--extra-steps", type=int, default=20)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU's share of the tensor-parallel layer; the blocks other "
@@ -148,9 +148,19 @@ def main() -> int:
                 if key not in memo:
                     memo[key] = peer(pair)
                 return memo[key]
-            base["da_row"] = {i: peer_memo(p) for i, p in inp["peers_dx"].items()}
-            base["da_col"] = {i: peer_memo(p) for i, p in inp["peers_dw"].items()}
+            if not cfg.second_linear:
+                base["da_row"] = {i: peer_memo(p) for i, p in inp["peers_dx"].items()}
+                base["da_col"] = {i: peer_memo(p) for i, p in inp["peers_dw"].items()}
             torch.cuda.synchronize()
+        second = cfg.second_linear
+        if second:
+            # saved pre-activation of the previous layer for this rank's dX block: [m, k] bf16
+            import math
+            own = inp["dx"]["out"]
+            base["a1"] = up(S.normal_block_bf16(S.BASE_SEED, S.T_PEER_A, dims[1], own[0] * m, m, own[1] * k, k,
+                                                0.02 * math.sqrt(dims[1])))
+            base["g_row"] = {i: up(p[0]) for i, p in inp["peers_dx"].items()}
+            base["g_col"] = {i: up(p[0]) for i, p in inp["peers_dw"].items()}
         for s in range(NSETS):
             def cp(v):
                 if s == 0:
@@ -162,6 +172,21 @@ def main() -> int:
                 return v.clone()
             b = {k_: cp(v) for k_, v in base.items()}
             o = dict(y=empty((m, n), f32y), pre=empty((m, n)), ws=ws_for(grid, dims))
+            if second:
+                calls = [("fwd NN +bias", one, gemm_symbol("NN", 1, f32y), lambda b=b, o=o: T.tp_linear_fwd(
+                    grid, dims, sf, b["x"], b["w"], b["bias"], T.EPI_BIAS, o["y"], None, o["ws"]))]
+                o.update(dx=empty((m, k)), dw=empty((k, n), True))
+                rows = [b["g"] if i == inp["own_slot_dx"] else b["g_row"][i] for i in range(sx)]
+                cols = [b["g"] if i == inp["own_slot_dw"] else b["g_col"][i] for i in range(sw)]
+                calls += [
+                    ("dX NT *GeLU'", one, gemm_symbol("NT", 3, False), lambda b=b, o=o, rows=rows: T.tp_linear_bwd(
+                        grid, dims, sx, 0, da_row_blocks=rows, w_blocks_dx=b["wdx"], dgelu_preact=b["a1"], dx=o["dx"],
+                        workspace=o["ws"])),
+                    ("dW TN", one, gemm_symbol("TN", 0, True), lambda b=b, o=o, cols=cols: T.tp_linear_bwd(
+                        grid, dims, 0, sw, x_blocks_dw=b["xdw"], da_col_blocks=cols, dw=o["dw"], workspace=o["ws"])),
+                ]
+                sets.append(calls)
+                continue
             calls = [("fwd NN +bias+GeLU", one, gemm_symbol("NN", 2, f32y), lambda b=b, o=o: T.tp_linear_fwd(
                 grid, dims, sf, b["x"], b["w"], b["bias"], T.EPI_BIAS_GELU, o["y"], o["pre"], o["ws"]))]
             if cfg.backward:
@@ -213,8 +238,22 @@ def main() -> int:
         torch.cuda.empty_cache()
         return res
 
+    def mfma_only_ceiling():
+        """Dense bf16 MFMA rate the chip sustains with nothing else running (register-resident loop)."""
+        scratch = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
+        best = 0.0
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            flops = T.tp_mfma_probe(scratch, 40000)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            best = max(best, flops / e0.elapsed_time(e1) / 1e9)
+        return round(best, 1)
+
     cfg = WL.config(args.config)
     main_res = run_config(cfg, args.steps, args.warmup)
+    mfma_only = mfma_only_ceiling()
 
     # dominant kernel = the kernel symbol with the largest share of the step
     by_sym = {}
@@ -228,7 +267,8 @@ def main() -> int:
     roofline = dict(bound="mfma", kernel=kname, launches_per_step=len(lst), avg_launch_ms=round(avg_ms, 4),
                     flops_per_launch=flops_per_launch, achieved=round(achieved, 1), peak=PEAK_BF16_TFLOPS,
                     unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4),
-                    traffic=MEASURED_TRAFFIC_BYTES.get(kname))
+                    traffic=MEASURED_TRAFFIC_BYTES.get(kname),
+                    measured_mfma_only_tflops=mfma_only, frac_of_measured_mfma_only=round(achieved / mfma_only, 4))
 
     cpu = None
     if not args.no_cpu:
@@ -239,7 +279,7 @@ def main() -> int:
         for c in WL.CONFIGS:
             if c.name == cfg.name:
                 continue
-            extra.append(run_config(c, args.extra_steps, 3))
+            extra.append(run_config(c, args.extra_steps, 5))
 
     out = {
         "metric": "bf16 TFLOP/s of per-rank TP linear fwd+bwd; % of MFMA dense peak",

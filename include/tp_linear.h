@@ -149,6 +149,16 @@ int tp_dgelu(const void* dy, int64_t ld_dy, const void* preact, int64_t ld_pre,
              void* da, int64_t ld_da, int64_t rows, int64_t cols, void* hip_stream);
 
 /*
+ * tp_mfma_probe -- measurement aid, not part of the layer: enqueues a register-resident loop of
+ * dense bf16 MFMAs (no LDS, no memory traffic, operands with random-looking bits) on every CU and
+ * reports in *flops (a HOST pointer, written before the call returns) how many floating-point
+ * operations the launch performs.  Timed by the caller, it gives the dense-bf16 rate this chip
+ * really sustains at the clock it holds under load, to set beside the published 2.5 PFLOP/s.
+ * scratch: device buffer of at least 256 x 256 x 4 bytes, 16-byte aligned (receives checksums).
+ */
+int tp_mfma_probe(void* scratch, size_t scratch_bytes, int iters, double* flops, void* hip_stream);
+
+/*
  * tp_plan_override -- tuning hook for benchmarks and tests.  key 0: macro-tile id (0 = automatic,
  * 1 = 256x256, 2 = 128x256, 3 = 256x128, 4 = 128x128); key 1: split-K factor (0 = automatic, 1..8);
  * key 2: tile-order group height in tile rows (0 = automatic, 1..64); key 3: rotate the K-tile

@@ -4,5 +4,5 @@ does, and fails loudly if it has not been built (python -m paper_2110_14883_amd.
 from .binding import (  # noqa: F401
     EPI_BIAS, EPI_BIAS_GELU, EPI_NONE, MODE_1D_COL, MODE_1D_ROW, MODE_2D, MODE_2P5D, MODE_3D,
     PASS_DW, PASS_DX, PASS_FWD, Grid, TpError, lib, tp_block_map, tp_dgelu, tp_linear_bwd,
-    tp_linear_fwd, tp_linear_workspace_size, tp_plan_override, tp_strerror,
+    tp_linear_fwd, tp_linear_workspace_size, tp_mfma_probe, tp_plan_override, tp_strerror,
 )

@@ -79,6 +79,8 @@ def lib() -> C.CDLL:
         L.tp_dgelu.restype = C.c_int
         L.tp_dgelu.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                C.c_int64, C.c_int64, C.c_void_p]
+        L.tp_mfma_probe.restype = C.c_int
+        L.tp_mfma_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.POINTER(C.c_double), C.c_void_p]
         L.tp_plan_override.restype = C.c_int
         L.tp_plan_override.argtypes = [C.c_int, C.c_int]
         L.tp_strerror.restype = C.c_char_p
@@ -88,7 +90,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ("tp_block_map", "tp_linear_workspace_size", "tp_linear_fwd", "tp_linear_bwd", "tp_dgelu",
-           "tp_plan_override", "tp_strerror")
+           "tp_mfma_probe", "tp_plan_override", "tp_strerror")
 
 
 # ----------------------------------------------------------------------------- marshalling helpers
@@ -228,6 +230,14 @@ def tp_dgelu(dy, preact, da, rows: int | None = None, cols: int | None = None, s
     a, b, c = _cblk(dy), _cblk(preact), _cblk(da)
     st = lib().tp_dgelu(a.ptr, a.ld, b.ptr, b.ld, c.ptr, c.ld, int(rows), int(cols), _stream(stream))
     _check(st, "tp_dgelu")
+
+
+def tp_mfma_probe(scratch, iters: int, stream=None) -> float:
+    """Enqueues the MFMA-only loop; returns the number of flops the launch performs."""
+    flops = C.c_double()
+    ws, wsb = _ws(scratch)
+    _check(lib().tp_mfma_probe(ws, wsb, int(iters), C.byref(flops), _stream(stream)), "tp_mfma_probe")
+    return flops.value
 
 
 def tp_plan_override(key: int, value: int) -> None:

@@ -352,6 +352,17 @@ int tp_dgelu(const void* dy, int64_t ld_dy, const void* preact, int64_t ld_pre, 
     return TP_OK;
 }
 
+int tp_mfma_probe(void* scratch, size_t scratch_bytes, int iters, double* flops, void* hip_stream) {
+    if (!scratch || !flops) return TP_ERR_NULL;
+    if (iters < 1) return TP_ERR_SHAPE;
+    if (scratch_bytes < (size_t)kCUs * 256 * sizeof(float) || !aligned16(scratch)) return TP_ERR_WORKSPACE;
+    // 256 workgroups x 4 waves x iters x 8 MFMAs of 32x32x16 (32768 flops each)
+    *flops = (double)kCUs * 4.0 * (double)iters * 8.0 * 32768.0;
+    if (launch_mfma_probe(static_cast<float*>(scratch), kCUs, iters, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return TP_ERR_HIP;
+    return TP_OK;
+}
+
 int tp_plan_override(int key, int value) {
     switch (key) {
         case 0: if (value < 0 || value > TILE_128x128) return TP_ERR_MODE; g_tile_override = value; return TP_OK;

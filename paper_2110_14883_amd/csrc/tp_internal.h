@@ -53,6 +53,7 @@ hipError_t launch_gemm(int form, int tile_id, const GemmArgs& args, hipStream_t 
 hipError_t launch_reduce(const ReduceArgs& args, hipStream_t stream);
 hipError_t launch_dgelu(const void* dy, int64_t ld_dy, const void* pre, int64_t ld_pre,
                         void* da, int64_t ld_da, int64_t rows, int64_t cols, hipStream_t stream);
+hipError_t launch_mfma_probe(float* out, int workgroups, int iters, hipStream_t stream);
 hipError_t launch_colsum(const void* da, int64_t ld, int64_t rows, int64_t cols, float* out, hipStream_t stream);
 
 }  // namespace tpl

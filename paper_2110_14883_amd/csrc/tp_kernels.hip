@@ -534,6 +534,36 @@ __global__ __launch_bounds__(256) void tp_colsum_kernel(const uint16_t* da, int6
 }
 
 // ---------------------------------------------------------------------------------------------
+// measurement aid: register-resident MFMA-only loop (no LDS, no memory), operands with random-looking
+// bits.  What it sustains is the chip's real dense-bf16 ceiling at the clock it holds under load.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void tp_mfma_probe_kernel(float* out, int iters, uint32_t seed) {
+    u32x4_t a0, b0;
+    uint32_t x = seed ^ (threadIdx.x * 2654435761u) ^ (blockIdx.x * 40503u);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x = x * 1664525u + 1013904223u; a0[i] = (x & 0x807f807fu) | 0x3f003f00u;     // bf16 pairs in [0.5, 1) with random sign/mantissa
+        x = x * 1664525u + 1013904223u; b0[i] = (x & 0x807f807fu) | 0x3c003c00u;
+    }
+    const bf16x8_t a = __builtin_bit_cast(bf16x8_t, a0), b = __builtin_bit_cast(bf16x8_t, b0);
+    f32x16_t acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s += acc[i][v];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------------------------
 void tile_shape(int tile_id, int* bm, int* bn) {
@@ -593,6 +623,11 @@ hipError_t launch_gemm(int form, int tile_id, const GemmArgs& a, hipStream_t s) 
         case TILE_128x128: return launch_tile<128, 128>(form, a, s);
         default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t launch_mfma_probe(float* out, int workgroups, int iters, hipStream_t s) {
+    hipLaunchKernelGGL(tp_mfma_probe_kernel, dim3((unsigned)workgroups), dim3(256), 0, s, out, iters, 0x9E3779B9u);
+    return hipGetLastError();
 }
 
 hipError_t launch_reduce(const ReduceArgs& a, hipStream_t s) {

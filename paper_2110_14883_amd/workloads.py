@@ -32,6 +32,8 @@ class Config:
     dx_dtype: str = "bf16"
     backward: bool = True
     chain_1d: bool = False         # 1D feed-forward chain: two weights, see make_mlp1d_inputs
+    second_linear: bool = False    # the down-projection of an MLP: bias-only forward, fp32 Y, and in backward
+                                   # GeLU'(A1) of the previous layer fused into dX's epilogue (no separate dA pass)
     note: str = ""
     extra: dict = field(default_factory=dict)
 
@@ -49,6 +51,8 @@ CONFIGS = [
            note="2.5D q=2 d=2 rank (1,0,1), ViT-style MLP, ragged local M = 32896"),
     Config("c5_3d_p2", B.Grid(B.MODE_3D, p=2, ri=1, rj=0, rk=1), (16384, 12288, 49152), n_steps=1,
            note="3D p=2 rank (1,0,1), GPT-3-175B-shaped MLP, literal single local product"),
+    Config("n1_2d_q4_fc2", B.Grid(B.MODE_2D, q=4, ri=1, rj=2), (8192, 32768, 8192), second_linear=True, y_dtype="f32",
+           note="the second linear (F -> H) of config 3's MLP: bias-only forward, dX with fused GeLU' epilogue, dW"),
     Config("c5x_3d_p2_exact", B.Grid(B.MODE_3D, p=2, ri=1, rj=0, rk=1), (16384, 12288, 49152),
            note="as c5 with both steps of the exact share"),
 ]

@@ -105,6 +105,8 @@ def test_gelu_tails_and_strided_blocks():
 def test_mlp1d_chain_small():
     _mlp1d(2, 1, 200, 136, 2 * 264, rows=None)
     _mlp1d(3, 0, 520, 264, 3 * 72, rows=None)
+    with overrides(split=2):            # the GeLU' epilogue through the split-K fix-up kernel
+        _mlp1d(2, 0, 300, 264, 2 * 136, rows=None)
 
 
 def _mlp1d(size, rank, M, H, F, rows, w_rows=None):
@@ -160,6 +162,84 @@ def _mlp1d(size, rank, M, H, F, rows, w_rows=None):
     torch.cuda.synchronize()
     check(host64(dX[sel]), bw["dX"], "bf16" if chained else "f32", "dX partial")
     check(host64(dW1[wsel]), bw["dW1"], "bf16" if chained else "f32", "dW1")
+
+
+# ----------------------------------------------------------------------------- the second linear of an MLP, and projections
+CHAIN = [
+    ("2d_q2", T.Grid(T.MODE_2D, q=2, ri=1, rj=0), O.Grid(O.MODE_2D, q=2, ri=1, rj=0), (2 * 264, 2 * 136, 2 * 392)),
+    ("2p5d_q2_d2", T.Grid(T.MODE_2P5D, q=2, d=2, ri=0, rj=1, rk=1), O.Grid(O.MODE_2P5D, q=2, d=2, ri=0, rj=1, rk=1), (4 * 72, 2 * 72, 2 * 264)),
+    ("3d_p2", T.Grid(T.MODE_3D, p=2, ri=1, rj=1, rk=0), O.Grid(O.MODE_3D, p=2, ri=1, rj=1, rk=0), (4 * 130, 2 * 72, 2 * 328)),
+]
+
+
+@pytest.mark.parametrize("name,grid,ogrid,dims", CHAIN, ids=[c[0] for c in CHAIN])
+def test_second_linear_with_fused_dgelu(name, grid, ogrid, dims):
+    """The down-projection of an MLP through the same entry points: forward with a bias-only epilogue,
+    backward dX with GeLU'(A1) fused as its epilogue (no separate elementwise pass) and dW2."""
+    M, H, F = dims                       # layer 1: H -> F;  layer 2: F -> H
+    say(f"[case] MLP second linear {name} M={M} H={H} F={F}")
+    d2 = (M, F, H)
+    seed = 4242
+    X = f64(S.normal_block_bf16(seed, S.T_X, H, 0, M, 0, H, 1.0))
+    W1 = f64(S.normal_block_bf16(seed, S.T_W1, F, 0, H, 0, F, 0.05))
+    b1 = f64(S.normal_block_bf16(seed, S.T_B1, F, 0, 1, 0, F, 0.05)[0])
+    W2b = S.normal_block_bf16(seed, S.T_W2, H, 0, F, 0, H, 0.05)
+    b2b = S.normal_block_bf16(seed, S.T_B1 + 20, H, 0, 1, 0, H, 0.05)[0]
+    G2b = S.normal_block_bf16(seed, S.T_G, H, 0, M, 0, H, 1.0)
+    W2, b2, G2 = f64(W2b), f64(b2b), f64(G2b)
+    A1, Zf = O.layer_fwd(X, W1, b1)                    # layer 1, unpartitioned, with its rounding points
+    A1s, Z = O.round_to_bf16(A1), O.round_to_bf16(Zf)
+    rc, kc, cc = O.chunk_counts(ogrid)                 # layer 2 chunk grid: Z [rc x kc], W2 [kc x cc]
+    fm, xm, wm_ = (T.tp_block_map(grid, d2, p_) for p_ in (0, 1, 2))
+    up = lambda a: dev(O.f64_to_bf16_bits(a))
+    ws = workspace_for(grid, d2)
+    # forward: Y2 = Z W2 + b2 (fp32 out)
+    y2 = torch.empty((fm["m"], fm["n"]), dtype=torch.float32, device="cuda")
+    T.tp_linear_fwd(grid, d2, fm["n_steps"], [up(O.chunk(Z, rc, kc, *a)) for a in fm["a"]],
+                    [up(O.chunk(W2, kc, cc, *b)) for b in fm["b"]], up(O.chunk(b2, 1, cc, 0, fm["out"][1])),
+                    T.EPI_BIAS, y2, None, ws)
+    torch.cuda.synchronize()
+    check(host64(y2), O.rank_fwd(ogrid, Z, W2, b2, act=False)[1], "f32", "Y2")
+    # backward: dA1 = bf16((sum_k dY2 W2^T) * GeLU'(A1_saved)) as the dX epilogue;  dW2 = sum_k Z^T dY2
+    own_a1 = O.chunk(A1s, rc, kc, *xm["out"])
+    da1 = torch.empty((xm["m"], xm["n"]), dtype=torch.bfloat16, device="cuda")
+    dw2 = torch.empty((wm_["m"], wm_["n"]), dtype=torch.float32, device="cuda")
+    T.tp_linear_bwd(grid, d2, xm["n_steps"], wm_["n_steps"],
+                    da_row_blocks=[up(O.chunk(G2, rc, cc, *a)) for a in xm["a"]],
+                    w_blocks_dx=[up(O.chunk(W2, kc, cc, *b)) for b in xm["b"]],
+                    x_blocks_dw=[up(O.chunk(Z, rc, kc, *a)) for a in wm_["a"]],
+                    da_col_blocks=[up(O.chunk(G2, rc, cc, *b)) for b in wm_["b"]],
+                    dgelu_preact=up(own_a1), dx=da1, dw=dw2, workspace=ws)
+    torch.cuda.synchronize()
+    dZ = O.rank_dx(ogrid, G2, W2)
+    check(host64(da1), O.round_to_bf16(dZ * O.dgelu(own_a1)), "bf16", "dA1 (dX with GeLU' epilogue)")
+    check(host64(dw2), O.rank_dw(ogrid, Z, G2), "f32", "dW2")
+
+
+def test_attention_projection_shapes():
+    """QKV (H -> 3H) and output projection (H -> H) shares: bias-only forward, backward without activation."""
+    for label, grid, dims in (("qkv 2d q2", T.Grid(T.MODE_2D, q=2, ri=0, rj=1), (2 * 200, 2 * 128, 2 * 384)),
+                              ("out-proj 3d p2", T.Grid(T.MODE_3D, p=2, ri=0, rj=1, rk=1), (4 * 100, 2 * 128, 2 * 128))):
+        run_share(grid, dims, epi=T.EPI_BIAS, backward=False, y_dtype="bf16", label=label + " fwd")
+        run_linear_backward(grid, dims, label=label + " bwd")
+
+
+def run_linear_backward(grid, dims, label=""):
+    """Backward of a layer without activation: the upstream gradient blocks are the 'dA' blocks."""
+    say(f"[case] {label} grid={grid} dims={dims}")
+    inp = WL.make_share_inputs(grid, dims, 99, None, True)
+    sx, sw = inp["n_steps_dx"], inp["n_steps_dw"]
+    gx = {inp["own_slot_dx"]: inp["g_own"], **{i: g for i, (g, a) in inp["peers_dx"].items()}}
+    gw = {inp["own_slot_dw"]: inp["g_own"], **{i: g for i, (g, a) in inp["peers_dw"].items()}}
+    mx, mw = T.tp_block_map(grid, dims, T.PASS_DX), T.tp_block_map(grid, dims, T.PASS_DW)
+    dx = torch.empty((mx["m"], mx["n"]), dtype=torch.bfloat16, device="cuda")
+    dw = torch.empty((mw["m"], mw["n"]), dtype=torch.float32, device="cuda")
+    T.tp_linear_bwd(grid, dims, sx, sw, da_row_blocks=[dev(gx[i]) for i in range(sx)],
+                    w_blocks_dx=[dev(b) for b in inp["w_blocks_dx"]], x_blocks_dw=[dev(b) for b in inp["x_blocks_dw"]],
+                    da_col_blocks=[dev(gw[i]) for i in range(sw)], dx=dx, dw=dw, workspace=workspace_for(grid, dims))
+    torch.cuda.synchronize()
+    check(host64(dx), O.share_dx([f64(gx[i]) for i in range(sx)], [f64(b) for b in inp["w_blocks_dx"]]), "bf16", "dX")
+    check(host64(dw), O.share_dw([f64(b) for b in inp["x_blocks_dw"]], [f64(gw[i]) for i in range(sw)]), "f32", "dW")
 
 
 # ----------------------------------------------------------------------------- the benchmark shares at full size
