@@ -29,7 +29,9 @@ continues from the rounded value.
 
 Parity pins for every function here are in tests/test_oracle_pins.py (brute
 force in pure Python, finite differences, closed forms, special cases,
-Table 1's count, exhaustive bf16 round trip).
+Table 1's count for the forward and for both backward products in their
+partials form, the two 3D readings against each other and against the plain
+layer, exhaustive bf16 round trip).
 """
 from __future__ import annotations
 
@@ -283,6 +285,96 @@ def assemble(ranks, pass_, blocks, shape):
         h, w = shape[0] // nr, shape[1] // nc
         out[r * h:(r + 1) * h, c * w:(c + 1) * w] += blk
     return out
+
+
+# ----------------------------------------------------------------------------- backward as partials for other owners (2D, 2.5D)
+def partials_map(g: Grid, pass_: int) -> dict:
+    """The other SUMMA form of the two backward products on a 2D / 2.5D grid: the rank's own dA
+    block stays where it is, one block of the other operand arrives per step, and every step's
+    product is an additive partial of a block that some rank of the same row (dX) or column (dW)
+    group owns.  This is the form whose traffic the communication-volume table of Section 3.1
+    counts for 2D and 2.5D: per product, (side - 1) blocks of the moving operand in and
+    (side - 1) partial blocks out.
+
+    Returns dict(own=(row, col) of the dA block, other=[block ids of the moving operand],
+    out=[block ids the partials belong to]).
+    dX: partial_k = dA[r, j] W[k, j]^T   belongs to dX[r, k]   (summed over j by the row group)
+    dW: partial_k = X[r, k]^T dA[r, j]   belongs to dW[k, j]   (summed over r by the column group
+                                                               and, in 2.5D, over the depth layers)
+    """
+    if g.mode not in (MODE_2D, MODE_2P5D):
+        raise ValueError("partials form exists for 2D and 2.5D grids only")
+    q, j = g.q, g.rj
+    r = (g.rk if g.mode == MODE_2P5D else 0) * q + g.ri
+    if pass_ == PASS_DX:
+        return dict(own=(r, j), other=[(k, j) for k in range(q)], out=[(r, k) for k in range(q)])
+    if pass_ == PASS_DW:
+        return dict(own=(r, j), other=[(r, k) for k in range(q)], out=[(k, j) for k in range(q)])
+    raise ValueError(pass_)
+
+
+def rank_dx_partials(g: Grid, dA, W):
+    """[(block id of dX, partial)] for rank g; the partials of one block id, summed over the ranks
+    that emit it, are that block of dX = dA W^T."""
+    check_grid(g, dA.shape[0], W.shape[0], W.shape[1])
+    rc, kc, cc = chunk_counts(g)
+    mp = partials_map(g, PASS_DX)
+    own = chunk(dA, rc, cc, *mp["own"])
+    return [(o, own @ chunk(W, kc, cc, *wb).T) for wb, o in zip(mp["other"], mp["out"])]
+
+
+def rank_dw_partials(g: Grid, X, dA):
+    check_grid(g, X.shape[0], X.shape[1], dA.shape[1])
+    rc, kc, cc = chunk_counts(g)
+    mp = partials_map(g, PASS_DW)
+    own = chunk(dA, rc, cc, *mp["own"])
+    return [(o, chunk(X, rc, kc, *xb).T @ own) for xb, o in zip(mp["other"], mp["out"])]
+
+
+# ----------------------------------------------------------------------------- 3D at its gathered local shape
+def gathered3d_map(g: Grid, pass_: int) -> dict:
+    """3D with the operands as they are after the all-gathers: ONE local product per pass on
+    slabs of shape [P/p, Q/p] (Section 2.2: the stored chunk is [P/p^2, Q/p]; gathering along
+    one cube axis undoes the second split of the first dimension), whose result is a partial
+    that a reduce-scatter along another axis would sum and split back into [P/p^2, .] chunks.
+    Block ids are in units of the gathered slabs: M in p slabs, H in p, F in p.
+
+    fwd: P = X[i, l] W[l, j]      partial of (X W)[i, j]   over l
+    dX : P = dA[i, j] W[l, j]^T   partial of dX[i, l]      over j
+    dW : P = X[i, l]^T dA[i, j]   partial of dW[l, j]      over i
+    Row chunk l of the summed forward slab (i, j) is the block the owner-computes reading
+    gives rank (i, j, l): row chunk i p + l of p^2.
+    """
+    if g.mode != MODE_3D:
+        raise ValueError("3D grids only")
+    i, j, l = g.ri, g.rj, g.rk
+    if pass_ == PASS_FWD:
+        return dict(a=(i, l), b=(l, j), out=(i, j))
+    if pass_ == PASS_DX:
+        return dict(a=(i, j), b=(l, j), out=(i, l))
+    if pass_ == PASS_DW:
+        return dict(a=(i, l), b=(i, j), out=(l, j))
+    raise ValueError(pass_)
+
+
+def rank3d_gathered(g: Grid, pass_: int, X=None, W=None, dA=None):
+    """(block id, partial) of rank g's single gathered-shape product, cut from the full tensors."""
+    p = g.p
+    mp = gathered3d_map(g, pass_)
+    if pass_ == PASS_FWD:
+        check_grid(g, X.shape[0], X.shape[1], W.shape[1])
+        return mp["out"], chunk(X, p, p, *mp["a"]) @ chunk(W, p, p, *mp["b"])
+    if pass_ == PASS_DX:
+        check_grid(g, dA.shape[0], W.shape[0], W.shape[1])
+        return mp["out"], chunk(dA, p, p, *mp["a"]) @ chunk(W, p, p, *mp["b"]).T
+    check_grid(g, X.shape[0], X.shape[1], dA.shape[1])
+    return mp["out"], chunk(X, p, p, *mp["a"]).T @ chunk(dA, p, p, *mp["b"])
+
+
+def bias_gelu(C, bias=None, act=True):
+    """What follows the summation of forward partials: A = C + b, Y = GeLU(A).  Returns (A, Y)."""
+    A = C if bias is None else C + bias[None, :]
+    return A, (gelu(A) if act else A)
 
 
 # ----------------------------------------------------------------------------- 1D MLP chain (Megatron feed-forward)

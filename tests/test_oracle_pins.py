@@ -262,6 +262,104 @@ def test_2d_map_moves_table1_volume(golden_dir):
         assert 3 * moved == eval(expr, {}, dict(j=j, Sx=Sx, Sw=Sw))
 
 
+def test_backward_partials_move_table1_volume(golden_dir):
+    """Table 1, 2D and 2.5D rows: each of the two backward products moves as much as the forward one,
+    (side-1)(Sx+Sw) (2.5D: (side-1)(Sx/d+Sw) per depth layer), when dA stays put, one block of the
+    other operand arrives per step and the partial products travel to their owners.  Counted from
+    the partials map: operand blocks that are not the rank's own plus partials owned by another rank."""
+    rows = dict((r[0], r[1]) for r in _golden(golden_dir, "table1_comm_volume.txt"))
+    fig = dict(kv.split("=") for kv in rows["fig"].split())
+    h, s, b = int(fig["h"]), int(fig["s"]), int(fig["b"])
+    Sx, Sw = b * s * h, h * h
+    for q, d in ((1, 1), (2, 1), (4, 1), (2, 2), (4, 2), (2, 4)):
+        mode = O.MODE_2D if d == 1 else O.MODE_2P5D
+        ranks = O.all_ranks(mode, q=q, d=d)
+        xb = (b * s // (q * d)) * (h // q)             # elements of one X / dX / dA block
+        wb = (h // q) * (h // q)
+        for pass_ in (O.PASS_DX, O.PASS_DW):
+            moved = 0
+            for g in ranks:
+                mp = O.partials_map(g, pass_)
+                r = mp["own"][0]
+                stored_w, stored_x = (g.ri, g.rj), (r, g.rj)     # what rank (i, j[, layer]) keeps of W and of X / dX
+                if pass_ == O.PASS_DX:                           # W blocks in, dX partials out
+                    moved += sum(wb for k in mp["other"] if k != stored_w)
+                    moved += sum(xb for o in mp["out"] if o != stored_x)
+                else:                                            # X blocks in, dW partials out
+                    moved += sum(xb for k in mp["other"] if k != stored_x)
+                    moved += sum(wb for o in mp["out"] if o != stored_w)
+            per_product = eval(rows["2D"] if d == 1 else rows["2.5D"], {}, dict(j=q, k=q, d=d, Sx=Sx, Sw=Sw)) / 3
+            assert moved == (per_product if d == 1 else per_product * d)      # 2.5D row is per depth layer
+
+
+def test_backward_partials_sum_to_the_plain_gradients():
+    """Every partial placed on the block it belongs to and summed: dX = dA W^T, dW = X^T dA."""
+    M, H, F = 24, 12, 16
+    X, W, b, G = _tiny(M, H, F)
+    A, Y = O.layer_fwd(X, W, b)
+    dA, dX, dW, _ = O.layer_bwd(X, W, A, G)
+    for mode, q, d in ((O.MODE_2D, 2, 1), (O.MODE_2P5D, 2, 3), (O.MODE_2D, 4, 1), (O.MODE_2P5D, 2, 2), (O.MODE_2D, 1, 1)):
+        ranks = O.all_ranks(mode, q=q, d=d)
+        gx, gw = np.zeros((M, H)), np.zeros((H, F))
+        for g in ranks:
+            rc, kc, cc = O.chunk_counts(g)
+            for (r, c), P in O.rank_dx_partials(g, dA, W):
+                hh, ww = M // rc, H // kc
+                assert P.shape == (hh, ww)
+                gx[r * hh:(r + 1) * hh, c * ww:(c + 1) * ww] += P
+            for (r, c), P in O.rank_dw_partials(g, X, dA):
+                hh, ww = H // kc, F // cc
+                assert P.shape == (hh, ww)
+                gw[r * hh:(r + 1) * hh, c * ww:(c + 1) * ww] += P
+        assert np.allclose(gx, dX, rtol=0, atol=1e-12)
+        assert np.allclose(gw, dW, rtol=0, atol=1e-12)
+    # one rank, by hand: rank (1, 0) of a 2 x 2 grid, dX partial for owner (1, 1) is dA[1,0] W[1,0]^T
+    g = O.Grid(O.MODE_2D, q=2, ri=1, rj=0)
+    parts = dict(O.rank_dx_partials(g, dA, W))
+    assert np.allclose(parts[(1, 1)], dA[12:, :8] @ W[6:, :8].T, atol=1e-13)
+    parts = dict(O.rank_dw_partials(g, X, dA))
+    assert np.allclose(parts[(1, 0)], X[12:, 6:].T @ dA[12:, :8], atol=1e-13)
+    with pytest.raises(ValueError):
+        O.partials_map(O.Grid(O.MODE_3D, p=2), O.PASS_DX)
+    with pytest.raises(ValueError):
+        O.partials_map(g, O.PASS_FWD)
+
+
+def test_3d_gathered_products_sum_to_the_layer_and_match_the_owner_reading():
+    """The single gathered-shape product per rank: partials summed over the cube axis they are
+    partial over give X W, dA W^T, X^T dA; row chunk l of the summed forward slab (i, j), with
+    bias and GeLU applied, is what the owner-computes 3D share of rank (i, j, l) holds."""
+    p, M, H, F = 2, 16, 8, 12
+    X, W, b, G = _tiny(M, H, F)
+    A, Y = O.layer_fwd(X, W, b)
+    dA, dX, dW, _ = O.layer_bwd(X, W, A, G)
+    ranks = O.all_ranks(O.MODE_3D, p=p)
+    full = {O.PASS_FWD: (np.zeros((M, F)), X @ W, M // p, F // p),
+            O.PASS_DX: (np.zeros((M, H)), dX, M // p, H // p),
+            O.PASS_DW: (np.zeros((H, F)), dW, H // p, F // p)}
+    for g in ranks:
+        for pass_, (acc, _, hh, ww) in full.items():
+            (r, c), P = O.rank3d_gathered(g, pass_, X=X, W=W, dA=dA)
+            assert P.shape == (hh, ww)
+            acc[r * hh:(r + 1) * hh, c * ww:(c + 1) * ww] += P
+    for acc, ref, _, _ in full.values():
+        assert np.allclose(acc, ref, rtol=0, atol=1e-12)
+    summed = full[O.PASS_FWD][0]
+    for g in ranks:
+        i, j, l = g.ri, g.rj, g.rk
+        slab = summed[i * (M // p):(i + 1) * (M // p), j * (F // p):(j + 1) * (F // p)]
+        mine = slab[l * (M // p // p):(l + 1) * (M // p // p)]
+        a_ref, y_ref = O.rank_fwd(g, X, W, b)
+        a, y = O.bias_gelu(mine, b[j * (F // p):(j + 1) * (F // p)])
+        assert np.allclose(a, a_ref, atol=1e-12) and np.allclose(y, y_ref, atol=1e-12)
+    # shapes as the paper prints them: stored chunk [P/p^2, Q/p], gathered slab [P/p, Q/p]
+    g = O.Grid(O.MODE_3D, p=2, ri=1, rj=0, rk=1)
+    (_, P) = O.rank3d_gathered(g, O.PASS_FWD, X=X, W=W)
+    assert P.shape == (M // p, F // p) and O.rank_fwd(g, X, W, b)[0].shape == (M // p ** 2, F // p)
+    with pytest.raises(ValueError):
+        O.gathered3d_map(O.Grid(O.MODE_2D, q=2), O.PASS_FWD)
+
+
 def test_grid_rule_rejects_bad_grids():
     with pytest.raises(ValueError):
         O.check_grid(O.Grid(O.MODE_2D, q=2, ri=2), 8, 8, 8)
