@@ -56,12 +56,17 @@ typedef enum {
     TP_MODE_1D_ROW = 11,   /* W cut by rows:    rank r owns W[r, :];  partial Y_r = X[:, r] W[r, :]      */
     TP_MODE_2D = 2,        /* q x q,      rank (ri, rj)                                                  */
     TP_MODE_2P5D = 25,     /* q x q x d,  rank (ri, rj, rk = depth layer)                                */
-    TP_MODE_3D = 3         /* p x p x p,  rank (ri, rj, rk)                                              */
+    TP_MODE_3D = 3,        /* p x p x p,  rank (ri, rj, rk)                                              */
+    TP_MODE_3D_GATHERED = 33 /* p x p x p with the operands as they are after the all-gathers: one product
+                              per pass on slabs [P/p, Q/p], every result a partial (see tp_block_map)   */
 } tp_mode_t;
 
 typedef enum { TP_BF16 = 0, TP_F32 = 1 } tp_dtype_t;
 typedef enum { TP_EPI_NONE = 0, TP_EPI_BIAS = 1, TP_EPI_BIAS_GELU = 2 } tp_epilogue_t;
-typedef enum { TP_PASS_FWD = 0, TP_PASS_DX = 1, TP_PASS_DW = 2 } tp_pass_t;
+typedef enum {
+    TP_PASS_FWD = 0, TP_PASS_DX = 1, TP_PASS_DW = 2,
+    TP_PASS_DX_PARTIALS = 3, TP_PASS_DW_PARTIALS = 4     /* tp_partials_map / tp_linear_bwd_partials only */
+} tp_pass_t;
 
 /* 1D: p = size, ri = rank (q = d = 1).  2D: q, (ri, rj).  2.5D: q, d, (ri, rj, rk).  3D: p, (ri, rj, rk).
  * Unused sizes must be 1 and unused coordinates 0. */
@@ -84,6 +89,11 @@ typedef struct { void* ptr; int64_t ld; int dtype; } tp_oblk_t;
  *   TP_PASS_FWD: C[m,n] = sum_k X[a_k] W[b_k];          out indexes Y (bias chunk = out_col)
  *   TP_PASS_DX : C[m,n] = sum_k dA[a_k] W[b_k]^T;       out indexes dX
  *   TP_PASS_DW : C[m,n] = sum_k X[a_k]^T dA[b_k];       out indexes dW
+ *   3D_GATHERED (Section 2.2: the stored chunk is [P/p^2, Q/p]; gathered along one cube axis it is
+ *     the slab [P/p, Q/p]): rc=kc=cc=p, one step per pass, every output a partial:
+ *       FWD: X[i,l] W[l,j] -> partial of (X W)[i,j] over l      DX: dA[i,j] W[l,j]^T -> dX[i,l] over j
+ *       DW : X[i,l]^T dA[i,j] -> dW[l,j] over i.   Bias and GeLU belong after the summation
+ *     (tp_bias_act); row chunk l of the summed slab (i,j) is rank (i,j,l)'s block under TP_MODE_3D.
  * m, n = extents of the output block, k_per_step = contraction length of one step.
  * a_row..b_col are host arrays of TP_MAX_STEPS ints (may be NULL if not wanted); *is_partial = 1
  * when the block is an additive partial that a reduction over other ranks would complete
@@ -95,10 +105,11 @@ int tp_block_map(const tp_grid_t* grid, const tp_dims_t* dims, int pass,
                  int* a_row, int* a_col, int* b_row, int* b_col,
                  int* out_row, int* out_col, int* is_partial);
 
-/* Bytes of device workspace tp_linear_fwd (pass TP_PASS_FWD) or tp_linear_bwd (TP_PASS_DX and
- * TP_PASS_DW each; pass the larger, the two products run one after the other) may need for this
- * share: cross-workgroup split-K partials in fp32.  0 on invalid arguments.  Never more than
- * 8 x m x n x 4 bytes. */
+/* Bytes of device workspace tp_linear_fwd (pass TP_PASS_FWD), tp_linear_bwd (TP_PASS_DX and
+ * TP_PASS_DW each; pass the larger, the two products run one after the other) or
+ * tp_linear_bwd_partials (TP_PASS_DX_PARTIALS, TP_PASS_DW_PARTIALS) may need for this share:
+ * cross-workgroup split-K partials in fp32.  0 on invalid arguments.  Never more than
+ * 8 x m x n x 4 bytes per product. */
 size_t tp_linear_workspace_size(const tp_grid_t* grid, const tp_dims_t* dims, int pass);
 
 /*
@@ -140,6 +151,52 @@ int tp_linear_bwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_dx, 
                   const tp_cblk_t* dgelu_preact,
                   tp_oblk_t dx, tp_oblk_t dw, tp_oblk_t da_own_out, void* db_f32,
                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * tp_partials_map -- the partition map of the backward products in their other SUMMA form, for 2D
+ * and 2.5D grids (host only).  The rank's own dA block (own_row, own_col) stays in place, one block
+ * of the other operand takes part per step, and step k's product is an additive partial of the
+ * block (out_row[k], out_col[k]) that another rank of the same row (dX) or column (dW) group owns.
+ * This is the form whose traffic Table 1 (Section 3.1) counts for 2D and 2.5D: per product,
+ * (side - 1) operand blocks in and (side - 1) partial blocks out.  Chunk grids as in tp_block_map.
+ *   TP_PASS_DX_PARTIALS: P_k[m,n] = dA[own] W[other_k]^T      out indexes dX;   m, n, k = M_blk, H_blk, F_blk
+ *   TP_PASS_DW_PARTIALS: P_k[m,n] = X[other_k]^T dA[own]      out indexes dW;   m, n, k = H_blk, F_blk, M_blk
+ * other_row .. out_col are host arrays of TP_MAX_STEPS ints (may be NULL).
+ * Errors: TP_ERR_NULL, TP_ERR_MODE (other modes or passes), TP_ERR_GRID, TP_ERR_SHAPE.
+ */
+int tp_partials_map(const tp_grid_t* grid, const tp_dims_t* dims, int pass,
+                    int* n_steps, int64_t* m, int64_t* n, int64_t* k,
+                    int* own_row, int* own_col, int* other_row, int* other_col,
+                    int* out_row, int* out_col);
+
+/*
+ * tp_linear_bwd_partials -- backward share in the form tp_partials_map describes: all n_dx (n_dw)
+ * products of a pass run in ONE launch whose tile grid covers every product, so a share whose
+ * single product has too few tiles for the chip still fills it.
+ *   da_own        : the rank's own dA block, bf16 [M_blk, F_blk].
+ *   w_blocks_dx   : host array [n_dx] of W blocks [H_blk, F_blk];  dx_partials: host array [n_dx] of
+ *                   fp32 outputs [M_blk, H_blk];  dx_partials[k] = da_own w_blocks_dx[k]^T.
+ *   x_blocks_dw   : host array [n_dw] of X blocks [M_blk, H_blk];  dw_partials: host array [n_dw] of
+ *                   fp32 outputs [H_blk, F_blk];  dw_partials[k] = x_blocks_dw[k]^T da_own.
+ *   n_dx, n_dw    : 0 (skip that pass) .. the map's step count; outputs must not overlap.
+ *   workspace     : >= max over the passes used of tp_linear_workspace_size(.., TP_PASS_D?_PARTIALS).
+ * Outputs are fp32 (they are summands of a reduction): TP_ERR_DTYPE otherwise.
+ */
+int tp_linear_bwd_partials(const tp_grid_t* grid, const tp_dims_t* dims, int n_dx, int n_dw,
+                           const tp_cblk_t* da_own,
+                           const tp_cblk_t* w_blocks_dx, const tp_oblk_t* dx_partials,
+                           const tp_cblk_t* x_blocks_dw, const tp_oblk_t* dw_partials,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * tp_bias_act -- what follows the summation of forward partials (1D_ROW and 3D_GATHERED outputs
+ * after their reduction):  A = c + bias,  y = GeLU(A) (epi TP_EPI_BIAS_GELU) or A (TP_EPI_BIAS) or c
+ * (TP_EPI_NONE: a dtype conversion).  c: fp32 [rows, cols] with leading dimension ld_c; bias: bf16
+ * [cols] or NULL with TP_EPI_NONE; y: fp32 or bf16; preact: optional bf16 copy of A.  cols and every
+ * ld multiples of 8.  HBM-bound.
+ */
+int tp_bias_act(const void* c, int64_t ld_c, const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact,
+                int64_t rows, int64_t cols, void* hip_stream);
 
 /*
  * tp_dgelu -- the elementwise part of backward on its own:  da = bf16(dy * GeLU'(preact)),

@@ -7,9 +7,9 @@ import ctypes as C
 import os
 from dataclasses import dataclass
 
-MODE_1D_COL, MODE_1D_ROW, MODE_2D, MODE_2P5D, MODE_3D = 10, 11, 2, 25, 3
+MODE_1D_COL, MODE_1D_ROW, MODE_2D, MODE_2P5D, MODE_3D, MODE_3D_GATHERED = 10, 11, 2, 25, 3, 33
 EPI_NONE, EPI_BIAS, EPI_BIAS_GELU = 0, 1, 2
-PASS_FWD, PASS_DX, PASS_DW = 0, 1, 2
+PASS_FWD, PASS_DX, PASS_DW, PASS_DX_PARTIALS, PASS_DW_PARTIALS = 0, 1, 2, 3, 4
 DT_BF16, DT_F32 = 0, 1
 MAX_STEPS = 16
 
@@ -76,6 +76,15 @@ def lib() -> C.CDLL:
                                     C.POINTER(_CBlk), C.POINTER(_CBlk), C.POINTER(_CBlk), C.POINTER(_CBlk),
                                     C.POINTER(_CBlk), C.POINTER(_CBlk), C.c_int, C.c_int, C.POINTER(_CBlk),
                                     _OBlk, _OBlk, _OBlk, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.tp_partials_map.restype = C.c_int
+        L.tp_partials_map.argtypes = [C.POINTER(_GridS), C.POINTER(_DimsS), C.c_int, ip, i64p, i64p, i64p,
+                                      ip, ip, ip, ip, ip, ip]
+        L.tp_linear_bwd_partials.restype = C.c_int
+        L.tp_linear_bwd_partials.argtypes = [C.POINTER(_GridS), C.POINTER(_DimsS), C.c_int, C.c_int, C.POINTER(_CBlk),
+                                             C.POINTER(_CBlk), C.POINTER(_OBlk), C.POINTER(_CBlk), C.POINTER(_OBlk),
+                                             C.c_void_p, C.c_size_t, C.c_void_p]
+        L.tp_bias_act.restype = C.c_int
+        L.tp_bias_act.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int, _OBlk, _OBlk, C.c_int64, C.c_int64, C.c_void_p]
         L.tp_dgelu.restype = C.c_int
         L.tp_dgelu.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                C.c_int64, C.c_int64, C.c_void_p]
@@ -90,6 +99,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ("tp_block_map", "tp_linear_workspace_size", "tp_linear_fwd", "tp_linear_bwd", "tp_dgelu",
+           "tp_partials_map", "tp_linear_bwd_partials", "tp_bias_act",
            "tp_mfma_probe", "tp_plan_override", "tp_strerror")
 
 
@@ -126,6 +136,15 @@ def _cblk_array(blocks, n):
     arr = (_CBlk * max(n, len(blocks), 1))()
     for i, b in enumerate(blocks):
         arr[i] = _cblk(b)
+    return arr
+
+
+def _oblk_array(blocks, n):
+    if blocks is None:
+        return None
+    arr = (_OBlk * max(n, len(blocks), 1))()
+    for i, b in enumerate(blocks):
+        arr[i] = _oblk(b)
     return arr
 
 
@@ -230,6 +249,42 @@ def tp_dgelu(dy, preact, da, rows: int | None = None, cols: int | None = None, s
     a, b, c = _cblk(dy), _cblk(preact), _cblk(da)
     st = lib().tp_dgelu(a.ptr, a.ld, b.ptr, b.ld, c.ptr, c.ld, int(rows), int(cols), _stream(stream))
     _check(st, "tp_dgelu")
+
+
+def tp_partials_map(grid: Grid, dims, pass_: int) -> dict:
+    n_steps, own_row, own_col = C.c_int(), C.c_int(), C.c_int()
+    m, n, k = C.c_int64(), C.c_int64(), C.c_int64()
+    arrs = [(C.c_int * MAX_STEPS)() for _ in range(4)]
+    g, d = grid._c(), _dims(dims)
+    st = lib().tp_partials_map(C.byref(g), C.byref(d), int(pass_), C.byref(n_steps), C.byref(m), C.byref(n), C.byref(k),
+                               C.byref(own_row), C.byref(own_col), arrs[0], arrs[1], arrs[2], arrs[3])
+    _check(st, "tp_partials_map")
+    s = n_steps.value
+    return dict(n_steps=s, m=m.value, n=n.value, k=k.value, own=(own_row.value, own_col.value),
+                other=[(arrs[0][i], arrs[1][i]) for i in range(s)], out=[(arrs[2][i], arrs[3][i]) for i in range(s)])
+
+
+def tp_linear_bwd_partials(grid: Grid, dims, da_own, w_blocks_dx=None, dx_partials=None, x_blocks_dw=None,
+                           dw_partials=None, workspace=None, stream=None) -> None:
+    g, d = grid._c(), _dims(dims)
+    ws, wsb = _ws(workspace)
+    n_dx = 0 if w_blocks_dx is None else len(w_blocks_dx)
+    n_dw = 0 if x_blocks_dw is None else len(x_blocks_dw)
+    if (dx_partials is not None and len(dx_partials) != n_dx) or (dw_partials is not None and len(dw_partials) != n_dw):
+        raise ValueError("one output block per operand block")
+    st = lib().tp_linear_bwd_partials(C.byref(g), C.byref(d), n_dx, n_dw, _cblk_ptr(da_own),
+                                      _cblk_array(w_blocks_dx, n_dx), _oblk_array(dx_partials, n_dx),
+                                      _cblk_array(x_blocks_dw, n_dw), _oblk_array(dw_partials, n_dw),
+                                      ws, wsb, _stream(stream))
+    _check(st, "tp_linear_bwd_partials")
+
+
+def tp_bias_act(c, bias, epi: int, y, preact=None, rows: int | None = None, cols: int | None = None, stream=None) -> None:
+    if rows is None:
+        rows, cols = int(c.shape[0]), int(c.shape[1])
+    ptr, ld = (c.data_ptr(), _ld(c)) if _is_tensor(c) else (int(c[0]), int(c[1]))
+    st = lib().tp_bias_act(ptr or None, ld, _ptr(bias), int(epi), _oblk(y), _oblk(preact), int(rows), int(cols), _stream(stream))
+    _check(st, "tp_bias_act")
 
 
 def tp_mfma_probe(scratch, iters: int, stream=None) -> float:

@@ -28,6 +28,7 @@ int check_grid(const tp_grid_t* g, Chunks* c) {
         case TP_MODE_2D:     li = lj = g->q; *c = {g->q, g->q, g->q}; if (g->p != 1 || g->d != 1) return TP_ERR_GRID; break;
         case TP_MODE_2P5D:   li = lj = g->q; lk = g->d; *c = {g->q * g->d, g->q, g->q}; if (g->p != 1) return TP_ERR_GRID; break;
         case TP_MODE_3D:     li = lj = lk = g->p; *c = {g->p * g->p, g->p, g->p}; if (g->q != 1 || g->d != 1) return TP_ERR_GRID; break;
+        case TP_MODE_3D_GATHERED: li = lj = lk = g->p; *c = {g->p, g->p, g->p}; if (g->q != 1 || g->d != 1) return TP_ERR_GRID; break;
         default: return TP_ERR_MODE;
     }
     if (g->ri < 0 || g->ri >= li || g->rj < 0 || g->rj >= lj || g->rk < 0 || g->rk >= lk) return TP_ERR_GRID;
@@ -47,8 +48,18 @@ int build_share(const tp_grid_t* g, const tp_dims_t* d, int pass, Share* s) {
     if (int e = check_grid(g, &c)) return e;
     if (d->M < 1 || d->H < 1 || d->F < 1) return TP_ERR_SHAPE;
     if (d->M % c.rc || d->H % c.kc || d->F % c.cc) return TP_ERR_SHAPE;
+    // the gathered slabs are made of p stored chunks [M/p^2, .]
+    if (g->mode == TP_MODE_3D_GATHERED && d->M % ((int64_t)g->p * g->p)) return TP_ERR_SHAPE;
     const int64_t mb = d->M / c.rc, hb = d->H / c.kc, fb = d->F / c.cc;
     std::memset(s, 0, sizeof(*s));
+    if (g->mode == TP_MODE_3D_GATHERED) {
+        const int i = g->ri, j = g->rj, l = g->rk;
+        s->n_steps = 1; s->partial = g->p > 1;
+        if (pass == TP_PASS_FWD)     { s->m = mb; s->n = fb; s->k = hb; s->a_row[0] = i; s->a_col[0] = l; s->b_row[0] = l; s->b_col[0] = j; s->out_row = i; s->out_col = j; }
+        else if (pass == TP_PASS_DX) { s->m = mb; s->n = hb; s->k = fb; s->a_row[0] = i; s->a_col[0] = j; s->b_row[0] = l; s->b_col[0] = j; s->out_row = i; s->out_col = l; }
+        else                         { s->m = hb; s->n = fb; s->k = mb; s->a_row[0] = i; s->a_col[0] = l; s->b_row[0] = i; s->b_col[0] = j; s->out_row = l; s->out_col = j; }
+        return TP_OK;
+    }
     int steps = 1, row = 0, col = 0, wrow = 0;     // own row chunk, own column index, dW's row chunk
     int first_row = 0;                             // first row chunk of the group dW sums over
     switch (g->mode) {
@@ -87,12 +98,41 @@ int build_share(const tp_grid_t* g, const tp_dims_t* d, int pass, Share* s) {
     return TP_OK;
 }
 
-struct Plan { int tile_id, bm, bn, tiles_m, tiles_n, split_k, group_m; };
+struct PartialsShare {   // the backward products as partials for other owners (2D, 2.5D)
+    int n_steps; int64_t m, n, k;
+    int own_row, own_col;
+    int other_row[TP_MAX_STEPS], other_col[TP_MAX_STEPS], out_row[TP_MAX_STEPS], out_col[TP_MAX_STEPS];
+};
+
+int build_partials(const tp_grid_t* g, const tp_dims_t* d, int pass, PartialsShare* s) {
+    if (!g || !d || !s) return TP_ERR_NULL;
+    if (pass != TP_PASS_DX_PARTIALS && pass != TP_PASS_DW_PARTIALS) return TP_ERR_MODE;
+    if (g->mode != TP_MODE_2D && g->mode != TP_MODE_2P5D) return TP_ERR_MODE;
+    Chunks c;
+    if (int e = check_grid(g, &c)) return e;
+    if (d->M < 1 || d->H < 1 || d->F < 1) return TP_ERR_SHAPE;
+    if (d->M % c.rc || d->H % c.kc || d->F % c.cc) return TP_ERR_SHAPE;
+    if (g->q > TP_MAX_STEPS) return TP_ERR_GRID;
+    const int64_t mb = d->M / c.rc, hb = d->H / c.kc, fb = d->F / c.cc;
+    std::memset(s, 0, sizeof(*s));
+    const int row = (g->mode == TP_MODE_2P5D ? g->rk * g->q : 0) + g->ri, col = g->rj;
+    s->n_steps = g->q; s->own_row = row; s->own_col = col;
+    for (int k = 0; k < g->q; ++k) {
+        if (pass == TP_PASS_DX_PARTIALS) { s->other_row[k] = k; s->other_col[k] = col; s->out_row[k] = row; s->out_col[k] = k; }
+        else                             { s->other_row[k] = row; s->other_col[k] = k; s->out_row[k] = k; s->out_col[k] = col; }
+    }
+    if (pass == TP_PASS_DX_PARTIALS) { s->m = mb; s->n = hb; s->k = fb; }
+    else                             { s->m = hb; s->n = fb; s->k = mb; }
+    return TP_OK;
+}
+
+struct Plan { int tile_id, bm, bn, tiles_m, tiles_n, split_k, group_m, groups; };
 
 // Pick the macro-tile and the split of K so that the launch fills whole waves of the 256 CUs.
 // Cost model: (waves of workgroups) x (K tiles per workgroup) x (tile area), plus the fp32
 // round trip of the partials when K is split.
-Plan make_plan(int64_t m, int64_t n, int64_t k, int n_steps) {
+// groups > 1: that many products of the same extents share one launch (tiles_m, tiles_n stay per product).
+Plan make_plan(int64_t m, int64_t n, int64_t k, int n_steps, int groups = 1) {
     const int64_t T = (int64_t)n_steps * ((k + 63) / 64);
     Plan best{};
     double best_cost = 1e300;
@@ -103,7 +143,7 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int n_steps) {
         int bm, bn;
         tile_shape(tile_ids[ti], &bm, &bn);
         const int64_t tm = (m + bm - 1) / bm, tn = (n + bn - 1) / bn;
-        const int64_t tiles = tm * tn;
+        const int64_t tiles = tm * tn * groups;
         // cycles one workgroup spends on one 64-deep K tile (measured: ~1.8 us at ~1.8 GHz for
         // 256x256); half and quarter tiles move more bytes per flop and measure ~1.3x / ~1.65x
         // slower per flop; every C tile also costs a fixed ~11 us (epilogue, pipeline refill)
@@ -116,16 +156,16 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int n_steps) {
             const int64_t waves = (tiles * z + kCUs - 1) / kCUs;
             const double main_cost = (double)waves * ((double)((T + z - 1) / z) * tile_cycles + per_tile);
             // partials: z fp32 planes written and read back at ~1.6 KB/clk, plus one more launch
-            const double fix = z > 1 ? (double)m * n * 8.0 * z / 1667.0 + 12000.0 : 0.0;
+            const double fix = z > 1 ? ((double)m * n * 8.0 * z / 1667.0 + 12000.0) * groups : 0.0;
             const double cost = main_cost + fix;
             if (cost < best_cost) {
                 best_cost = cost;
-                best = Plan{tile_ids[ti], bm, bn, (int)tm, (int)tn, z, 4};
+                best = Plan{tile_ids[ti], bm, bn, (int)tm, (int)tn, z, 4, groups};
             }
         }
     }
     if (best.tile_id == 0) {           // overrides left nothing admissible: fall back to the safe default
-        best = Plan{TILE_256x256, 256, 256, (int)((m + 255) / 256), (int)((n + 255) / 256), 1, 4};
+        best = Plan{TILE_256x256, 256, 256, (int)((m + 255) / 256), (int)((n + 255) / 256), 1, 4, groups};
     }
     const int go = g_group_override.load();
     best.group_m = go > 0 ? go : 4;
@@ -150,7 +190,7 @@ int check_oblk(const tp_oblk_t& b, int64_t cols, bool f32_only) {
 }
 
 size_t ws_bytes_for(const Plan& p, int64_t m, int64_t n) {
-    return p.split_k > 1 ? (size_t)p.split_k * (size_t)m * (size_t)n * sizeof(float) : 0;
+    return p.split_k > 1 ? (size_t)p.split_k * (size_t)p.groups * (size_t)m * (size_t)n * sizeof(float) : 0;
 }
 
 struct Product {                 // one validated GEMM ready to launch
@@ -162,8 +202,14 @@ int run_product(const Product& pr, void* workspace, hipStream_t stream) {
     a.ws = static_cast<float*>(workspace);
     if (launch_gemm(pr.form, pr.plan.tile_id, a, stream) != hipSuccess) return TP_ERR_HIP;
     if (pr.plan.split_k > 1) {
-        ReduceArgs r{a.ws, a.split_k, a.M, a.N, a.out, a.ldo, a.out_f32, a.pre, a.ldp, a.bias, a.gelu, a.dg, a.lddg};
-        if (launch_reduce(r, stream) != hipSuccess) return TP_ERR_HIP;
+        const int groups = a.n_groups > 1 ? a.n_groups : 1;
+        const int64_t mn = (int64_t)a.M * a.N;
+        for (int g = 0; g < groups; ++g) {
+            void* out = groups > 1 ? a.outs[g] : a.out;
+            const int64_t ldo = groups > 1 ? a.ldos[g] : a.ldo;
+            ReduceArgs r{a.ws + g * mn, mn * groups, a.split_k, a.M, a.N, out, ldo, a.out_f32, a.pre, a.ldp, a.bias, a.gelu, a.dg, a.lddg};
+            if (launch_reduce(r, stream) != hipSuccess) return TP_ERR_HIP;
+        }
     }
     return TP_OK;
 }
@@ -202,6 +248,16 @@ int tp_block_map(const tp_grid_t* grid, const tp_dims_t* dims, int pass, int* n_
 }
 
 size_t tp_linear_workspace_size(const tp_grid_t* grid, const tp_dims_t* dims, int pass) {
+    if (pass == TP_PASS_DX_PARTIALS || pass == TP_PASS_DW_PARTIALS) {
+        PartialsShare ps;
+        if (build_partials(grid, dims, pass, &ps) != TP_OK) return 0;
+        size_t worst = 0;
+        for (int groups = 1; groups <= ps.n_steps; ++groups)
+            worst = std::max(worst, ws_bytes_for(make_plan(ps.m, ps.n, ps.k, 1, groups), ps.m, ps.n));
+        if (g_split_override.load() > 1)
+            worst = std::max(worst, (size_t)g_split_override.load() * ps.n_steps * ps.m * ps.n * sizeof(float));
+        return worst;
+    }
     Share s;
     if (build_share(grid, dims, pass, &s) != TP_OK) return 0;
     // independent of overrides and of n_steps: the bound every plan respects (split <= 8 only when
@@ -226,6 +282,10 @@ int tp_linear_fwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps, con
     if (epi != TP_EPI_NONE && epi != TP_EPI_BIAS && epi != TP_EPI_BIAS_GELU) return TP_ERR_MODE;
     if (epi != TP_EPI_NONE && !bias) return TP_ERR_NULL;
     if (bias && !aligned16(bias)) return TP_ERR_ALIGN;
+    if (grid->mode == TP_MODE_3D_GATHERED) {      // a partial over a cube axis: bias and GeLU come after the summation
+        if (epi != TP_EPI_NONE || preact.ptr) return TP_ERR_MODE;
+        if (y.ptr && y.dtype != TP_F32) return TP_ERR_DTYPE;
+    }
     if (s.m > INT32_MAX || s.n > INT32_MAX || s.k > INT32_MAX) return TP_ERR_SHAPE;
     for (int k = 0; k < n_steps; ++k) {
         if (int e = check_cblk(x_blocks[k], s.k)) return e;
@@ -337,6 +397,101 @@ int tp_linear_bwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_dx, 
     }
     if (px.active) if (int e = run_product(px, workspace, stream)) return e;
     if (pw.active) if (int e = run_product(pw, workspace, stream)) return e;
+    return TP_OK;
+}
+
+int tp_partials_map(const tp_grid_t* grid, const tp_dims_t* dims, int pass, int* n_steps, int64_t* m, int64_t* n,
+                    int64_t* k, int* own_row, int* own_col, int* other_row, int* other_col, int* out_row, int* out_col) {
+    PartialsShare s;
+    if (int e = build_partials(grid, dims, pass, &s)) return e;
+    if (n_steps) *n_steps = s.n_steps;
+    if (m) *m = s.m;
+    if (n) *n = s.n;
+    if (k) *k = s.k;
+    if (own_row) *own_row = s.own_row;
+    if (own_col) *own_col = s.own_col;
+    for (int i = 0; i < TP_MAX_STEPS; ++i) {
+        if (other_row) other_row[i] = s.other_row[i];
+        if (other_col) other_col[i] = s.other_col[i];
+        if (out_row) out_row[i] = s.out_row[i];
+        if (out_col) out_col[i] = s.out_col[i];
+    }
+    return TP_OK;
+}
+
+int tp_linear_bwd_partials(const tp_grid_t* grid, const tp_dims_t* dims, int n_dx, int n_dw, const tp_cblk_t* da_own,
+                           const tp_cblk_t* w_blocks_dx, const tp_oblk_t* dx_partials, const tp_cblk_t* x_blocks_dw,
+                           const tp_oblk_t* dw_partials, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    PartialsShare sx, sw;
+    if (int e = build_partials(grid, dims, TP_PASS_DX_PARTIALS, &sx)) return e;
+    if (int e = build_partials(grid, dims, TP_PASS_DW_PARTIALS, &sw)) return e;
+    if (n_dx < 0 || n_dx > sx.n_steps || n_dw < 0 || n_dw > sw.n_steps) return TP_ERR_SHAPE;
+    if (sx.m > INT32_MAX || sx.n > INT32_MAX || sx.k > INT32_MAX) return TP_ERR_SHAPE;
+    if (n_dx == 0 && n_dw == 0) return TP_OK;
+    if (!da_own) return TP_ERR_NULL;
+    if (int e = check_cblk(*da_own, sx.k)) return e;                  // [M_blk, F_blk]
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    Product px{}; px.active = n_dx > 0;
+    if (px.active) {
+        if (!w_blocks_dx || !dx_partials) return TP_ERR_NULL;
+        Plan p = make_plan(sx.m, sx.n, sx.k, 1, n_dx);
+        fill_common(px.args, p, sx.m, sx.n, sx.k, 1);
+        for (int k = 0; k < n_dx; ++k) {
+            if (int e = check_cblk(w_blocks_dx[k], sx.k)) return e;    // W block [H_blk][F_blk]: n x k
+            if (int e = check_oblk(dx_partials[k], sx.n, true)) return e;
+            px.args.a[k] = da_own->ptr; px.args.lda[k] = (int32_t)da_own->ld;
+            px.args.b[k] = w_blocks_dx[k].ptr; px.args.ldb[k] = (int32_t)w_blocks_dx[k].ld;
+            px.args.outs[k] = dx_partials[k].ptr; px.args.ldos[k] = dx_partials[k].ld;
+        }
+        px.args.out = dx_partials[0].ptr; px.args.ldo = dx_partials[0].ld; px.args.out_f32 = 1;
+        px.args.n_groups = n_dx; px.args.group_along_n = 1; px.args.group_tiles = p.tiles_n;
+        px.args.tiles_n = p.tiles_n * n_dx;                            // the products side by side along N
+        px.form = FORM_NT; px.plan = p;
+    }
+    Product pw{}; pw.active = n_dw > 0;
+    if (pw.active) {
+        if (!x_blocks_dw || !dw_partials) return TP_ERR_NULL;
+        Plan p = make_plan(sw.m, sw.n, sw.k, 1, n_dw);
+        fill_common(pw.args, p, sw.m, sw.n, sw.k, 1);
+        for (int k = 0; k < n_dw; ++k) {
+            if (int e = check_cblk(x_blocks_dw[k], sw.m)) return e;    // X block [M_blk][H_blk]: k x m
+            if (int e = check_oblk(dw_partials[k], sw.n, true)) return e;
+            pw.args.a[k] = x_blocks_dw[k].ptr; pw.args.lda[k] = (int32_t)x_blocks_dw[k].ld;
+            pw.args.b[k] = da_own->ptr; pw.args.ldb[k] = (int32_t)da_own->ld;
+            pw.args.outs[k] = dw_partials[k].ptr; pw.args.ldos[k] = dw_partials[k].ld;
+        }
+        pw.args.out = dw_partials[0].ptr; pw.args.ldo = dw_partials[0].ld; pw.args.out_f32 = 1;
+        pw.args.n_groups = n_dw; pw.args.group_along_n = 0; pw.args.group_tiles = p.tiles_m;
+        pw.args.tiles_m = p.tiles_m * n_dw;                            // the products stacked along M
+        pw.form = FORM_TN; pw.plan = p;
+    }
+    size_t need = 0;
+    if (px.active) need = std::max(need, ws_bytes_for(px.plan, sx.m, sx.n));
+    if (pw.active) need = std::max(need, ws_bytes_for(pw.plan, sw.m, sw.n));
+    if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return TP_ERR_WORKSPACE;
+    if (px.active) if (int e = run_product(px, workspace, stream)) return e;
+    if (pw.active) if (int e = run_product(pw, workspace, stream)) return e;
+    return TP_OK;
+}
+
+int tp_bias_act(const void* c, int64_t ld_c, const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact, int64_t rows,
+                int64_t cols, void* hip_stream) {
+    if (!c || !y.ptr) return TP_ERR_NULL;
+    if (epi != TP_EPI_NONE && epi != TP_EPI_BIAS && epi != TP_EPI_BIAS_GELU) return TP_ERR_MODE;
+    if (epi != TP_EPI_NONE && !bias) return TP_ERR_NULL;
+    if (rows < 0 || cols < 0) return TP_ERR_SHAPE;
+    if (!aligned16(c) || (bias && !aligned16(bias)) || (ld_c & 7)) return TP_ERR_ALIGN;
+    if (ld_c < cols) return TP_ERR_SHAPE;
+    if (int e = check_oblk(y, cols, false)) return e;
+    if (preact.ptr) {
+        if (int e = check_oblk(preact, cols, false)) return e;
+        if (preact.dtype != TP_BF16) return TP_ERR_DTYPE;
+    }
+    if (launch_bias_act(static_cast<const float*>(c), ld_c, epi == TP_EPI_NONE ? nullptr : bias, epi == TP_EPI_BIAS_GELU,
+                        y.ptr, y.ld, y.dtype == TP_F32, preact.ptr, preact.ld, rows, cols,
+                        static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return TP_ERR_HIP;
     return TP_OK;
 }
 

@@ -35,10 +35,19 @@ struct GemmArgs {
     float* ws;                          // [split_k][M][N] fp32 partials
     int32_t rotate;                     // rotate the K-tile order inside a step per C tile
     int32_t max_workgroups;             // persistent grid size cap (workgroups resident at once)
+    // Grouped launch (n_groups > 1): n_groups independent single-step products of the same extents
+    // in one grid, product g = a[g] x b[g] -> outs[g] (no epilogue).  The groups are laid side by
+    // side along N (group_along_n) or along M in the tile grid: tiles_m / tiles_n then count the
+    // tiles of all groups together and group_tiles is one group's tile count along that axis.
+    // With split_k > 1 the partial planes are ws[(z * n_groups + g)][M][N].
+    int32_t n_groups, group_along_n, group_tiles;
+    void* outs[TP_MAX_STEPS];
+    int64_t ldos[TP_MAX_STEPS];
 };
 
 struct ReduceArgs {
-    const float* ws; int32_t split_k; int32_t M, N;
+    const float* ws; int64_t plane;      // first partial plane and the distance between planes, in floats
+    int32_t split_k; int32_t M, N;
     void* out;   int64_t ldo;   int32_t out_f32;
     void* pre;   int64_t ldp;
     const void* bias; int32_t gelu;
@@ -55,5 +64,8 @@ hipError_t launch_dgelu(const void* dy, int64_t ld_dy, const void* pre, int64_t 
                         void* da, int64_t ld_da, int64_t rows, int64_t cols, hipStream_t stream);
 hipError_t launch_mfma_probe(float* out, int workgroups, int iters, hipStream_t stream);
 hipError_t launch_colsum(const void* da, int64_t ld, int64_t rows, int64_t cols, float* out, hipStream_t stream);
+// y = [GeLU](c + bias) over an fp32 [rows][cols] block, optional bf16 copy of c + bias
+hipError_t launch_bias_act(const float* c, int64_t ldc, const void* bias, int gelu, void* y, int64_t ldy, int y_f32,
+                           void* pre, int64_t ldp, int64_t rows, int64_t cols, hipStream_t stream);
 
 }  // namespace tpl

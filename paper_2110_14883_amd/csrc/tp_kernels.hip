@@ -218,7 +218,7 @@ __device__ __forceinline__ void tile_of_id(const GemmArgs& p, const int lin, int
 
 template <int V> using KS = std::integral_constant<int, V>;
 
-struct TileCoord { int m0, n0, z, rot; };
+struct TileCoord { int m0, n0, z, rot, g; };
 
 // ---------------------------------------------------------------------------------------------
 // one wave group's part of the GEMM (IS_P: waves 0-3, stage A;  else waves 4-7, stage B)
@@ -250,10 +250,11 @@ __device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const in
     // Inside a step the K tiles are taken in a rotated order that differs from C tile to C tile, so
     // that the CUs of one XCD are not all asking the same memory channel for the same K offset.
     auto fetch = [&](const TileCoord& c, int tile) __attribute__((always_inline)) {
-        const int s = tile / KT;
-        int kt = tile - s * KT + c.rot;
+        const int st_ = tile / KT;
+        int kt = tile - st_ * KT + c.rot;
         if (kt >= KT) kt -= KT;
         const int k0 = kt * BK;
+        const int s = st_ + c.g;             // a grouped launch has one step per group: operand slot = group
         if constexpr (IS_P) {
             const uint16_t* ap = static_cast<const uint16_t*>(p.a[s]);
             if constexpr (A_KC) st.load(ap, p.lda[s], p.M, c.m0, p.K, k0, tg);
@@ -268,7 +269,12 @@ __device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const in
         int tm, tn, z;
         tile_of_id(p, v, tm, tn, z);
         const int rot = p.rotate ? ((tm * 3 + tn * 5) & 7) % KT : 0;
-        return TileCoord{tm * BM, tn * BN, z, rot};
+        int g = 0;
+        if (p.n_groups > 1) {
+            if (p.group_along_n) { g = tn / p.group_tiles; tn -= g * p.group_tiles; }
+            else                 { g = tm / p.group_tiles; tm -= g * p.group_tiles; }
+        }
+        return TileCoord{tm * BM, tn * BN, z, rot, g};
     };
 
     f32x16_t acc[TM][TN];
@@ -434,7 +440,7 @@ __device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const in
             };
 
             if (partial) {
-                float* const wsz = p.ws + (int64_t)z * p.M * p.N;
+                float* const wsz = p.ws + ((int64_t)z * p.n_groups + cur_tile.g) * p.M * p.N;
 #pragma unroll
                 for (int i = 0; i < TM; ++i) slab_f32(i, raw4, wsz, (int64_t)p.N);
             } else {
@@ -443,8 +449,8 @@ __device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const in
                     if constexpr (!use_dg) {
                         if (use_pre) slab_bf16(i, preact4, static_cast<uint16_t*>(p.pre), p.ldp);
                     }
-                    if constexpr (F32_OUT) slab_f32(i, final4, static_cast<float*>(p.out), p.ldo);
-                    else                   slab_bf16(i, final4, static_cast<uint16_t*>(p.out), p.ldo);
+                    if constexpr (F32_OUT) slab_f32(i, final4, static_cast<float*>(p.outs[cur_tile.g]), p.ldos[cur_tile.g]);
+                    else                   slab_bf16(i, final4, static_cast<uint16_t*>(p.outs[cur_tile.g]), p.ldos[cur_tile.g]);
                 }
             }
         }
@@ -470,7 +476,7 @@ __global__ __launch_bounds__(NTHREADS) void tp_gemm_kernel(const GemmArgs p) {
 __global__ __launch_bounds__(256) void tp_reduce_kernel(const ReduceArgs p) {
     const int n4 = p.N >> 2;
     const int64_t total = (int64_t)p.M * n4;
-    const int64_t plane = (int64_t)p.M * p.N;
+    const int64_t plane = p.plane;
     Epilogue e{p.out, p.ldo, p.out_f32, p.pre, p.ldp, p.bias, p.gelu, p.dg, p.lddg};
     for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
          idx += (int64_t)gridDim.x * blockDim.x) {
@@ -505,6 +511,40 @@ __global__ __launch_bounds__(256) void tp_dgelu_kernel(const uint16_t* dy, int64
         for (int i = 0; i < 4; ++i)
             o[i] = pack_bf16(bf16_lo(g[i]) * dgelu_f(bf16_lo(a[i])), bf16_hi(g[i]) * dgelu_f(bf16_hi(a[i])));
         *reinterpret_cast<u32x4_t*>(da + r * ld_da + c) = o;
+    }
+}
+
+// y = [GeLU](c + bias) over an fp32 block (what follows the summation of forward partials),
+// optional bf16 copy of c + bias; 4 elements per thread per trip
+__global__ __launch_bounds__(256) void tp_bias_act_kernel(const float* c, int64_t ldc, const uint16_t* bias, int gelu,
+                                                          void* y, int64_t ldy, int y_f32, uint16_t* pre, int64_t ldp,
+                                                          int64_t rows, int cols4) {
+    const int64_t total = rows * cols4;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = idx / cols4;
+        const int n = (int)(idx - r * cols4) * 4;
+        const f32x4_t x = *reinterpret_cast<const f32x4_t*>(c + r * ldc + n);
+        float v[4] = {x[0], x[1], x[2], x[3]};
+        if (bias) {
+            const u32x2_t b = *reinterpret_cast<const u32x2_t*>(bias + n);
+            v[0] += bf16_lo(b[0]); v[1] += bf16_hi(b[0]); v[2] += bf16_lo(b[1]); v[3] += bf16_hi(b[1]);
+        }
+        if (pre) {
+            const u32x2_t s = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+            *reinterpret_cast<u32x2_t*>(pre + r * ldp + n) = s;
+        }
+        if (gelu) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = gelu_f(v[i]);
+        }
+        if (y_f32) {
+            const f32x4_t o = {v[0], v[1], v[2], v[3]};
+            *reinterpret_cast<f32x4_t*>(static_cast<float*>(y) + r * ldy + n) = o;
+        } else {
+            const u32x2_t o = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+            *reinterpret_cast<u32x2_t*>(static_cast<uint16_t*>(y) + r * ldy + n) = o;
+        }
     }
 }
 
@@ -615,7 +655,15 @@ static hipError_t launch_tile(int form, const GemmArgs& a, hipStream_t s) {
     }
 }
 
-hipError_t launch_gemm(int form, int tile_id, const GemmArgs& a, hipStream_t s) {
+hipError_t launch_gemm(int form, int tile_id, const GemmArgs& args, hipStream_t s) {
+    GemmArgs a = args;
+    if (a.n_groups <= 1) {             // a plain launch is one group whose output is `out`
+        a.n_groups = 1; a.group_along_n = 1; a.group_tiles = a.tiles_n;
+        a.outs[0] = a.out; a.ldos[0] = a.ldo;
+    } else if (a.n_steps != 1 || a.n_groups > TP_MAX_STEPS || a.group_tiles < 1 || a.bias || a.dg || a.pre ||
+               (a.group_along_n ? a.tiles_n : a.tiles_m) != a.n_groups * a.group_tiles) {
+        return hipErrorInvalidValue;
+    }
     switch (tile_id) {
         case TILE_256x256: return launch_tile<256, 256>(form, a, s);
         case TILE_128x256: return launch_tile<128, 256>(form, a, s);
@@ -648,6 +696,17 @@ hipError_t launch_dgelu(const void* dy, int64_t ld_dy, const void* pre, int64_t 
     hipLaunchKernelGGL(tp_dgelu_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const uint16_t*>(dy), ld_dy,
                        static_cast<const uint16_t*>(pre), ld_pre, static_cast<uint16_t*>(da), ld_da, rows,
                        (int)(cols >> 3));
+    return hipGetLastError();
+}
+
+hipError_t launch_bias_act(const float* c, int64_t ldc, const void* bias, int gelu, void* y, int64_t ldy, int y_f32,
+                           void* pre, int64_t ldp, int64_t rows, int64_t cols, hipStream_t s) {
+    const int64_t total = rows * (cols >> 2);
+    if (total == 0) return hipSuccess;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(tp_bias_act_kernel, dim3((unsigned)blocks), dim3(256), 0, s, c, ldc, static_cast<const uint16_t*>(bias),
+                       gelu, y, ldy, y_f32, static_cast<uint16_t*>(pre), ldp, rows, (int)(cols >> 2));
     return hipGetLastError();
 }
 

@@ -134,6 +134,38 @@ def make_share_inputs(grid: B.Grid, dims, seed: int = S.BASE_SEED, n_steps: int 
     return out
 
 
+def make_partials_inputs(grid: B.Grid, dims, seed: int = S.BASE_SEED) -> dict:
+    """Blocks for the backward products in their partials form (2D / 2.5D): the rank's own dA block
+    (taken from the upstream-gradient generator: any bf16 block serves), the W blocks of its column
+    and the X blocks of its row, by the library's own map."""
+    M, H, F = dims
+    rc, kc, cc = _chunk_counts(grid)
+    mb, hb, fb = M // rc, H // kc, F // cc
+    dxm = B.tp_partials_map(grid, dims, B.PASS_DX_PARTIALS)
+    dwm = B.tp_partials_map(grid, dims, B.PASS_DW_PARTIALS)
+    r, c = dxm["own"]
+    return dict(grid=grid, dims=dims, dx=dxm, dw=dwm, m=mb, h=hb, f=fb,
+                da_own=S.normal_block_bf16(seed, S.T_G, F, r * mb, mb, c * fb, fb, 1.0),
+                w_blocks=[S.normal_block_bf16(seed, S.T_W1, F, wr * hb, hb, wc * fb, fb, 0.02) for wr, wc in dxm["other"]],
+                x_blocks=[S.normal_block_bf16(seed, S.T_X, H, xr * mb, mb, xc * hb, hb, 1.0) for xr, xc in dwm["other"]])
+
+
+def make_gathered3d_inputs(grid: B.Grid, dims, seed: int = S.BASE_SEED) -> dict:
+    """Slabs of the single gathered-shape product per pass of a 3D rank (grid.mode MODE_3D_GATHERED):
+    X slab, W block, dA slab (from the upstream-gradient generator)."""
+    M, H, F = dims
+    p = grid.p
+    ms, hb, fb = M // p, H // p, F // p
+    maps = {ps: B.tp_block_map(grid, dims, ps) for ps in (B.PASS_FWD, B.PASS_DX, B.PASS_DW)}
+    (xr, xc), (wr, wc) = maps[B.PASS_FWD]["a"][0], maps[B.PASS_FWD]["b"][0]
+    (gr, gc) = maps[B.PASS_DX]["a"][0]
+    return dict(grid=grid, dims=dims, maps=maps, m=ms, h=hb, f=fb,
+                x=S.normal_block_bf16(seed, S.T_X, H, xr * ms, ms, xc * hb, hb, 1.0),
+                w=S.normal_block_bf16(seed, S.T_W1, F, wr * hb, hb, wc * fb, fb, 0.02),
+                da=S.normal_block_bf16(seed, S.T_G, F, gr * ms, ms, gc * fb, fb, 1.0),
+                bias=S.normal_block_bf16(seed, S.T_B1, F, 0, 1, maps[B.PASS_FWD]["out"][1] * fb, fb, 0.02)[0])
+
+
 def make_mlp1d_inputs(size: int, rank: int, M: int, H: int, F: int, seed: int = S.BASE_SEED) -> dict:
     """Rank `rank` of a 1D feed-forward of `size` ranks: X [M,H], W1[:, r] [H, F/size], b1[r],
     W2[r, :] [F/size, H], upstream gradient G [M, H]."""

@@ -242,6 +242,137 @@ def run_linear_backward(grid, dims, label=""):
     check(host64(dw), O.share_dw([f64(b) for b in inp["x_blocks_dw"]], [f64(gw[i]) for i in range(sw)]), "f32", "dW")
 
 
+# ----------------------------------------------------------------------------- backward as partials for other owners
+def _ws_bytes(nbytes):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+
+
+def _partials(grid, dims, rows=None, w_rows=None, ws_bytes=None, label=""):
+    """tp_linear_bwd_partials against the oracle's single-step products of the same blocks."""
+    say(f"[case] partials {label} grid={grid} dims={dims} rows={'all' if rows is None else len(rows)}")
+    inp = WL.make_partials_inputs(grid, dims)
+    m, h, f = inp["m"], inp["h"], inp["f"]
+    q = inp["dx"]["n_steps"]
+    assert inp["dw"]["n_steps"] == q and len(inp["w_blocks"]) == q and len(inp["x_blocks"]) == q
+    da = dev(inp["da_own"])
+    w_d = [dev(b) for b in inp["w_blocks"]]
+    x_d = [dev(b) for b in inp["x_blocks"]]
+    dxp = [torch.full((m, h), float("nan"), dtype=torch.float32, device="cuda") for _ in range(q)]
+    dwp = [torch.full((h, f), float("nan"), dtype=torch.float32, device="cuda") for _ in range(q)]
+    if ws_bytes is None:
+        ws_bytes = max(T.tp_linear_workspace_size(grid, dims, ps) for ps in (T.PASS_DX_PARTIALS, T.PASS_DW_PARTIALS))
+    say("  launching")
+    T.tp_linear_bwd_partials(grid, dims, da, w_d, dxp, x_d, dwp, _ws_bytes(ws_bytes))
+    torch.cuda.synchronize()
+    da64 = f64(inp["da_own"])
+    sel = slice(None) if rows is None else rows
+    wsel = slice(None) if w_rows is None else w_rows
+    for k in range(q):
+        check(host64(dxp[k][sel]), O.share_dx([da64], [f64(inp["w_blocks"][k])], rows), "f32",
+              f"dX partial {k} for owner {inp['dx']['out'][k]}")
+        check(host64(dwp[k][wsel]), O.share_dw([f64(inp["x_blocks"][k])], [da64], w_rows), "f32",
+              f"dW partial {k} for owner {inp['dw']['out'][k]}")
+
+
+def test_bwd_partials_small():
+    _partials(T.Grid(T.MODE_2D, q=2, ri=1, rj=0), (2 * 300, 2 * 136, 2 * 328), label="2d q2")
+    _partials(T.Grid(T.MODE_2D, q=3, ri=2, rj=1), (3 * 264, 3 * 72, 3 * 200), label="2d q3")
+    _partials(T.Grid(T.MODE_2P5D, q=2, d=2, ri=0, rj=1, rk=1), (4 * 130, 2 * 264, 2 * 136), label="2.5d q2 d2")
+    _partials(T.Grid(T.MODE_2D, q=1), (257, 72, 8), label="q1: one product")
+
+
+@pytest.mark.parametrize("tile,split", [(1, 2), (2, 1), (3, 3), (4, 1), (4, 2)])
+def test_bwd_partials_tiles_and_split(tile, split):
+    grid, dims = T.Grid(T.MODE_2D, q=3, ri=0, rj=2), (3 * 392, 3 * 264, 3 * 520)
+    mx = T.tp_partials_map(grid, dims, T.PASS_DX_PARTIALS)
+    mw = T.tp_partials_map(grid, dims, T.PASS_DW_PARTIALS)
+    room = 8 * 3 * 4 * max(mx["m"] * mx["n"], mw["m"] * mw["n"])
+    with overrides(tile=tile, split=split):
+        _partials(grid, dims, ws_bytes=room, label=f"tile {tile} split {split}")
+
+
+def test_bwd_partials_single_pass_and_prefix():
+    """Only dX, only dW, and fewer products than the map has."""
+    grid, dims = T.Grid(T.MODE_2D, q=2, ri=0, rj=1), (2 * 200, 2 * 136, 2 * 264)
+    inp = WL.make_partials_inputs(grid, dims)
+    m, h, f = inp["m"], inp["h"], inp["f"]
+    da, da64 = dev(inp["da_own"]), f64(inp["da_own"])
+    ws = _ws_bytes(8 * 2 * 4 * max(m * h, h * f))
+    dxp = [torch.full((m, h), float("nan"), dtype=torch.float32, device="cuda")]
+    T.tp_linear_bwd_partials(grid, dims, da, [dev(inp["w_blocks"][1])], dxp, None, None, ws)
+    dwp = [torch.full((h, f), float("nan"), dtype=torch.float32, device="cuda") for _ in range(2)]
+    T.tp_linear_bwd_partials(grid, dims, da, None, None, [dev(b) for b in inp["x_blocks"]], dwp, ws)
+    torch.cuda.synchronize()
+    check(host64(dxp[0]), O.share_dx([da64], [f64(inp["w_blocks"][1])]), "f32", "dX partial alone")
+    for k in range(2):
+        check(host64(dwp[k]), O.share_dw([f64(inp["x_blocks"][k])], [da64]), "f32", f"dW partial {k} alone")
+
+
+# ----------------------------------------------------------------------------- 3D at its gathered local shape
+def _gathered3d(grid, dims, rows=None, w_rows=None, label=""):
+    say(f"[case] 3d gathered {label} grid={grid} dims={dims} rows={'all' if rows is None else len(rows)}")
+    inp = WL.make_gathered3d_inputs(grid, dims)
+    ms, hb, fb = inp["m"], inp["h"], inp["f"]
+    x, w, da = dev(inp["x"]), dev(inp["w"]), dev(inp["da"])
+    x64, w64, da64 = f64(inp["x"]), f64(inp["w"]), f64(inp["da"])
+    ws = workspace_for(grid, dims)
+    sel = slice(None) if rows is None else rows
+    wsel = slice(None) if w_rows is None else w_rows
+    y = torch.full((ms, fb), float("nan"), dtype=torch.float32, device="cuda")
+    dx = torch.full((ms, hb), float("nan"), dtype=torch.float32, device="cuda")
+    dw = torch.full((hb, fb), float("nan"), dtype=torch.float32, device="cuda")
+    say("  launching")
+    T.tp_linear_fwd(grid, dims, 1, [x], [w], None, T.EPI_NONE, y, None, ws)
+    T.tp_linear_bwd(grid, dims, 1, 1, da_row_blocks=[da], w_blocks_dx=[w], x_blocks_dw=[x], da_col_blocks=[da],
+                    dx=dx, dw=dw, workspace=ws)
+    torch.cuda.synchronize()
+    C, _ = O.share_fwd([x64], [w64], None, False, rows)
+    check(host64(y[sel]), C, "f32", "forward partial")
+    check(host64(dx[sel]), O.share_dx([da64], [w64], rows), "f32", "dX partial")
+    check(host64(dw[wsel]), O.share_dw([x64], [da64], w_rows), "f32", "dW partial")
+    # the rank's chunk of the (here: single-term) summed slab, then bias and GeLU
+    p, l = grid.p, grid.rk
+    mc = ms // p
+    mine = y[l * mc:(l + 1) * mc]
+    yb = torch.empty((mc, fb), dtype=torch.bfloat16, device="cuda")
+    pre = torch.empty((mc, fb), dtype=torch.bfloat16, device="cuda")
+    T.tp_bias_act(mine, dev(inp["bias"]), T.EPI_BIAS_GELU, yb, pre)
+    torch.cuda.synchronize()
+    if rows is None:
+        A, Y = O.bias_gelu(C[l * mc:(l + 1) * mc], f64(inp["bias"]))
+        check(host64(yb), Y, "bf16", "Y chunk after bias + GeLU")
+        check(host64(pre), A, "bf16", "A_saved chunk")
+
+
+def test_3d_gathered_small():
+    _gathered3d(T.Grid(T.MODE_3D_GATHERED, p=2, ri=1, rj=0, rk=1), (4 * 150, 2 * 136, 2 * 264), label="p2")
+    _gathered3d(T.Grid(T.MODE_3D_GATHERED, p=3, ri=2, rj=1, rk=0), (9 * 40, 3 * 72, 3 * 200), label="p3")
+    _gathered3d(T.Grid(T.MODE_3D_GATHERED, p=1), (130, 72, 8), label="p1")
+
+
+def test_bias_act_alone():
+    """fp32 input with full mantissas, every epilogue kind, both output dtypes, strided views."""
+    rows, cols = 70, 264
+    a = f64(S.normal_block_bf16(11, S.T_X, cols, 0, rows, 0, cols, 3.0)).astype(np.float32)
+    b = f64(S.normal_block_bf16(12, S.T_X, cols, 0, rows, 0, cols, 1.0)).astype(np.float32)
+    c32 = (a + b * np.float32(2.0 ** -9)).astype(np.float32)
+    bias_bits = S.normal_block_bf16(13, S.T_B1, cols, 0, 1, 0, cols, 0.5)[0]
+    big = torch.zeros((rows, cols + 24), dtype=torch.float32, device="cuda")
+    big[:, 8:8 + cols] = torch.from_numpy(c32).cuda()
+    c_d = big[:, 8:8 + cols]
+    c64 = c32.astype(np.float64)
+    for epi, act, use_b in ((T.EPI_BIAS_GELU, True, True), (T.EPI_BIAS, False, True), (T.EPI_NONE, False, False)):
+        A, Y = O.bias_gelu(c64, f64(bias_bits) if use_b else None, act)
+        for dt, kind in ((torch.float32, "f32"), (torch.bfloat16, "bf16")):
+            y = torch.zeros((rows, cols + 16), dtype=dt, device="cuda")
+            pre = torch.empty((rows, cols), dtype=torch.bfloat16, device="cuda")
+            T.tp_bias_act(c_d, dev(bias_bits) if use_b else None, epi, y[:, :cols], pre)
+            torch.cuda.synchronize()
+            check(host64(y[:, :cols]), Y, kind, f"bias_act epi {epi} {kind}")
+            check(host64(pre), A, "bf16", f"bias_act epi {epi} saved pre-activation")
+            assert float(y[:, cols:].abs().max()) == 0.0
+
+
 # ----------------------------------------------------------------------------- the benchmark shares at full size
 def test_config1_full():
     c = WL.config("c1_2d_q2_fwd")
@@ -262,3 +393,23 @@ def test_config2_full_size_sampled():
     M, H, F = c.dims
     _mlp1d(c.grid.p, c.grid.ri, M, H, F, rows=S.sample_rows(5, M, 192),
            w_rows=S.sample_rows(6, H, 96))
+
+
+def test_config3_partials_full_size_sampled():
+    """Config 3's backward in the partials form: four products per pass in one launch."""
+    c = WL.config("c3_2d_q4")
+    mx = T.tp_partials_map(c.grid, c.dims, T.PASS_DX_PARTIALS)
+    _partials(c.grid, c.dims, rows=S.sample_rows(7, mx["m"], 128), w_rows=S.sample_rows(8, mx["n"], 64), label=c.name)
+
+
+def test_config4_partials_full_size_sampled():
+    c = WL.config("c4_2p5d_q2_d2")
+    mx = T.tp_partials_map(c.grid, c.dims, T.PASS_DX_PARTIALS)
+    _partials(c.grid, c.dims, rows=S.sample_rows(9, mx["m"], 128), w_rows=S.sample_rows(10, mx["n"], 64), label=c.name)
+
+
+def test_config5_gathered_full_size_sampled():
+    c = WL.config("c5_3d_p2")
+    g = T.Grid(T.MODE_3D_GATHERED, p=c.grid.p, ri=c.grid.ri, rj=c.grid.rj, rk=c.grid.rk)
+    mp = T.tp_block_map(g, c.dims, 0)
+    _gathered3d(g, c.dims, rows=S.sample_rows(11, mp["m"], 128), w_rows=S.sample_rows(12, mp["k"], 64), label=c.name)

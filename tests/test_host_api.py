@@ -63,6 +63,34 @@ def test_block_map_agrees_with_the_oracle_map():
             assert (got["m"], got["n"], got["k"]) == {0: (mb, fb, hb), 1: (mb, hb, fb), 2: (hb, fb, mb)}[pass_]
 
 
+def test_partials_map_and_gathered_map_agree_with_the_oracle():
+    M, H, F = 8 * 36, 8 * 12, 8 * 24
+    for tg, og in _pairs():
+        if og.mode in (O.MODE_2D, O.MODE_2P5D):
+            rc, kc, cc = O.chunk_counts(og)
+            for tp, op in ((T.PASS_DX_PARTIALS, O.PASS_DX), (T.PASS_DW_PARTIALS, O.PASS_DW)):
+                got, ref = T.tp_partials_map(tg, (M, H, F), tp), O.partials_map(og, op)
+                assert got["own"] == ref["own"] and got["other"] == ref["other"] and got["out"] == ref["out"], (og, tp)
+                mb, hb, fb = M // rc, H // kc, F // cc
+                assert (got["m"], got["n"], got["k"]) == ((mb, hb, fb) if tp == T.PASS_DX_PARTIALS else (hb, fb, mb))
+        elif og.mode == O.MODE_3D:
+            g3 = T.Grid(T.MODE_3D_GATHERED, p=og.p, ri=og.ri, rj=og.rj, rk=og.rk)
+            p = og.p
+            for pass_ in (0, 1, 2):
+                got, ref = T.tp_block_map(g3, (M, H, F), pass_), O.gathered3d_map(og, pass_)
+                assert got["n_steps"] == 1 and got["a"] == [ref["a"]] and got["b"] == [ref["b"]] and got["out"] == ref["out"]
+                assert got["partial"] == (p > 1)
+                assert (got["m"], got["n"], got["k"]) == {0: (M // p, F // p, H // p), 1: (M // p, H // p, F // p),
+                                                           2: (H // p, F // p, M // p)}[pass_]
+        else:
+            assert _st(lambda: T.tp_partials_map(tg, (M, H, F), T.PASS_DX_PARTIALS)) == 2
+    assert _st(lambda: T.tp_partials_map(T.Grid(T.MODE_2D, q=2), (M, H, F), T.PASS_DX)) == 2
+    assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_2D, q=2), (M, H, F), T.PASS_DX_PARTIALS)) == 2
+    assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_3D_GATHERED, p=2), (8 * 2, 16, 16), 0)) == 0
+    assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_3D_GATHERED, p=2), (8 * 3 * 2, 16, 16), 0)) == 0     # 48 % 4 == 0
+    assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_3D_GATHERED, p=2), (2 * 7, 16, 16), 0)) == 4         # slabs not made of p chunks
+
+
 def test_config_block_shapes():
     """The five benchmark shares have the local extents their descriptions state."""
     from paper_2110_14883_amd import workloads as WL
@@ -134,6 +162,32 @@ def test_argument_errors_before_any_launch():
     assert _st(lambda: bw(dx=(0x60000, 64, B.DT_BF16), own_slot_dx=0)) == 1
     assert _st(lambda: bw(dx=(0x60000, 64, B.DT_BF16), db=0x70000)) == 1
     assert _st(lambda: T.tp_dgelu((0x10000, 0), (0x10000, 0), (0x10000, 0), 4, 12, stream=0)) in (4, 5)
+    # partials form: fp32 outputs only, one dA block, counts within the map
+    g2 = T.Grid(T.MODE_2D, q=2)
+    pb = lambda **kw: T.tp_linear_bwd_partials(g2, d, kw.get("da", (0x10000, 128)), kw.get("w", [(0x30000, 128)] * 2),
+                                               kw.get("dxp", [(0x60000, 64, B.DT_F32), (0x70000, 64, B.DT_F32)]),
+                                               kw.get("x", None), kw.get("dwp", None), None, stream=0)
+    assert _st(lambda: pb(dxp=[(0x60000, 64, B.DT_BF16), (0x70000, 64, B.DT_F32)])) == 6
+    assert _st(lambda: pb(da=(0, 128))) == 1
+    assert _st(lambda: pb(w=[(0x30000, 128)] * 3, dxp=[(0x60000, 64, B.DT_F32)] * 3)) == 4
+    assert _st(lambda: pb(w=[(0x30000, 120)] * 2)) == 4
+    assert _st(lambda: T.tp_linear_bwd_partials(T.Grid(T.MODE_3D, p=2), (64, 64, 64), (0x10000, 32), [(0x30000, 32)],
+                                                [(0x60000, 32, B.DT_F32)], stream=0)) == 2
+    # 3D gathered forward is a partial: no epilogue, fp32 only
+    g3 = T.Grid(T.MODE_3D_GATHERED, p=2)
+    f3 = lambda **kw: T.tp_linear_fwd(g3, (256, 128, 256), 1, [(0x10000, 64)], [(0x30000, 128)], kw.get("bias", None),
+                                      kw.get("epi", T.EPI_NONE), kw.get("y", (0x20000, 128, B.DT_F32)), none_o, None, stream=0)
+    assert _st(lambda: f3(epi=T.EPI_BIAS, bias=0x40000)) == 2
+    assert _st(lambda: f3(y=(0x20000, 128, B.DT_BF16))) == 6
+    # bias / activation pass
+    ba = lambda **kw: T.tp_bias_act(kw.get("c", (0x10000, 64)), kw.get("bias", 0x40000), kw.get("epi", T.EPI_BIAS_GELU),
+                                    kw.get("y", (0x20000, 64, B.DT_BF16)), kw.get("pre", None), 4, kw.get("cols", 64), stream=0)
+    assert _st(lambda: ba(c=(0, 64))) == 1
+    assert _st(lambda: ba(bias=0)) == 1
+    assert _st(lambda: ba(epi=5)) == 2
+    assert _st(lambda: ba(cols=60)) == 5
+    assert _st(lambda: ba(c=(0x10000, 56))) == 4
+    assert _st(lambda: ba(pre=(0x50000, 64, B.DT_F32))) == 6
     assert _st(lambda: T.tp_plan_override(9, 0)) == 2
     assert _st(lambda: T.tp_plan_override(1, 99)) == 2
     assert _st(lambda: T.tp_plan_override(0, 5)) == 2
