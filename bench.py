@@ -204,10 +204,61 @@ def main() -> int:
             sets.append(calls)
         return sets, one * (3 if cfg.backward else 1)
 
+    def build_partials(cfg):
+        """Forward as in the owner-computes share, backward as partials for other owners."""
+        grid, dims = cfg.grid, cfg.dims
+        fin = WL.make_share_inputs(grid, dims, S.BASE_SEED, None, False)
+        pin = WL.make_partials_inputs(grid, dims)
+        m, n, k, sf, q = fin["m"], fin["n"], fin["k"], fin["n_steps_fwd"], pin["dx"]["n_steps"]
+        one = 2.0 * m * n * k * sf
+        wsb = max([T.tp_linear_workspace_size(grid, dims, ps) for ps in (0, 3, 4)] + [256])
+        base = dict(x=[up(b) for b in fin["x_blocks"]], w=[up(b) for b in fin["w_blocks"]], bias=up(fin["bias"]),
+                    g=up(pin["da_own"]), wp=[up(b) for b in pin["w_blocks"]], xp=[up(b) for b in pin["x_blocks"]])
+        sets = []
+        for s in range(NSETS):
+            b = base if s == 0 else {k_: ([t.clone() for t in v] if isinstance(v, list) else v.clone()) for k_, v in base.items()}
+            o = dict(y=empty((m, n)), pre=empty((m, n)), da=empty((m, n)), ws=torch.empty(wsb, dtype=torch.uint8, device="cuda"),
+                     dxp=[empty((m, k), True) for _ in range(q)], dwp=[empty((k, n), True) for _ in range(q)])
+            sets.append([
+                ("fwd NN +bias+GeLU", one, gemm_symbol("NN", 2, False), lambda b=b, o=o: T.tp_linear_fwd(
+                    grid, dims, sf, b["x"], b["w"], b["bias"], T.EPI_BIAS_GELU, o["y"], o["pre"], o["ws"])),
+                ("dA = dY*GeLU'(A)", 0.0, "tpl::tp_dgelu_kernel", lambda b=b, o=o: T.tp_dgelu(b["g"], o["pre"], o["da"])),
+                (f"dX partials NT x{q}", one, gemm_symbol("NT", 0, True), lambda b=b, o=o: T.tp_linear_bwd_partials(
+                    grid, dims, o["da"], b["wp"], o["dxp"], None, None, o["ws"])),
+                (f"dW partials TN x{q}", one, gemm_symbol("TN", 0, True), lambda b=b, o=o: T.tp_linear_bwd_partials(
+                    grid, dims, o["da"], None, None, b["xp"], o["dwp"], o["ws"])),
+            ])
+        return sets, 3 * one
+
+    def build_gathered(cfg):
+        grid, dims = cfg.grid, cfg.dims
+        inp = WL.make_gathered3d_inputs(grid, dims)
+        ms, hb, fb, p, l = inp["m"], inp["h"], inp["f"], grid.p, grid.rk
+        mc = ms // p
+        one = 2.0 * ms * hb * fb
+        base = dict(x=up(inp["x"]), w=up(inp["w"]), da=up(inp["da"]), bias=up(inp["bias"]))
+        sets = []
+        for s in range(NSETS):
+            b = base if s == 0 else {k_: v.clone() for k_, v in base.items()}
+            o = dict(c=empty((ms, fb), True), y=empty((mc, fb)), pre=empty((mc, fb)), dx=empty((ms, hb), True),
+                     dw=empty((hb, fb), True), ws=ws_for(grid, dims))
+            sets.append([
+                ("fwd NN fp32 partial", one, gemm_symbol("NN", 0, True), lambda b=b, o=o: T.tp_linear_fwd(
+                    grid, dims, 1, [b["x"]], [b["w"]], None, T.EPI_NONE, o["c"], None, o["ws"])),
+                ("bias+GeLU on the rank's chunk", 0.0, "tpl::tp_bias_act_kernel", lambda b=b, o=o: T.tp_bias_act(
+                    o["c"][l * mc:(l + 1) * mc], b["bias"], T.EPI_BIAS_GELU, o["y"], o["pre"])),
+                ("dX NT fp32 partial", one, gemm_symbol("NT", 0, True), lambda b=b, o=o: T.tp_linear_bwd(
+                    grid, dims, 1, 0, da_row_blocks=[b["da"]], w_blocks_dx=[b["w"]], dx=o["dx"], workspace=o["ws"])),
+                ("dW TN fp32 partial", one, gemm_symbol("TN", 0, True), lambda b=b, o=o: T.tp_linear_bwd(
+                    grid, dims, 0, 1, x_blocks_dw=[b["x"]], da_col_blocks=[b["da"]], dw=o["dw"], workspace=o["ws"])),
+            ])
+        return sets, 3 * one
+
     def run_config(cfg, steps, warmup):
         log(f"[bench] {cfg.name}: generating inputs")
         t0 = time.time()
-        sets, flops = (build_mlp1d if cfg.chain_1d else build_share)(cfg)
+        builder = {"partials": build_partials, "gathered": build_gathered}.get(cfg.variant) or (build_mlp1d if cfg.chain_1d else build_share)
+        sets, flops = builder(cfg)
         log(f"[bench] {cfg.name}: inputs ready in {time.time() - t0:.1f}s; warmup {warmup}, steps {steps}")
         ncall = len(sets[0])
         for i in range(warmup):

@@ -34,6 +34,8 @@ class Config:
     chain_1d: bool = False         # 1D feed-forward chain: two weights, see make_mlp1d_inputs
     second_linear: bool = False    # the down-projection of an MLP: bias-only forward, fp32 Y, and in backward
                                    # GeLU'(A1) of the previous layer fused into dX's epilogue (no separate dA pass)
+    variant: str = ""              # "partials": backward as partials for other owners (tp_linear_bwd_partials);
+                                   # "gathered": 3D at its gathered local shape (one product per pass)
     note: str = ""
     extra: dict = field(default_factory=dict)
 
@@ -55,6 +57,13 @@ CONFIGS = [
            note="the second linear (F -> H) of config 3's MLP: bias-only forward, dX with fused GeLU' epilogue, dW"),
     Config("c5x_3d_p2_exact", B.Grid(B.MODE_3D, p=2, ri=1, rj=0, rk=1), (16384, 12288, 49152),
            note="as c5 with both steps of the exact share"),
+    Config("r3_2d_q4_partials", B.Grid(B.MODE_2D, q=4, ri=1, rj=2), (8192, 8192, 32768), variant="partials",
+           note="config 3 with the backward products as partials for other owners: 4 products per pass in one launch"),
+    Config("r4_2p5d_q2_d2_partials", B.Grid(B.MODE_2P5D, q=2, d=2, ri=1, rj=0, rk=1), (131584, 1280, 5120), variant="partials",
+           note="config 4 with the backward products as partials for other owners"),
+    Config("g5_3d_p2_gathered", B.Grid(B.MODE_3D_GATHERED, p=2, ri=1, rj=0, rk=1), (16384, 12288, 49152), variant="gathered",
+           note="config 5's layer at the gathered local shape: one 8192 x 6144 x 24576 product per pass, fp32 partials, "
+                "bias + GeLU on the rank's chunk afterwards"),
 ]
 
 
@@ -184,6 +193,10 @@ def gemm_flops(cfg_or_inputs) -> dict:
     """GEMM flops (2 m n k per product) of a share: forward, backward, total."""
     if isinstance(cfg_or_inputs, Config):
         c = cfg_or_inputs
+        if c.variant == "gathered":
+            f = B.tp_block_map(c.grid, c.dims, B.PASS_FWD)
+            one = 2.0 * f["m"] * f["n"] * f["k"]
+            return dict(fwd=one, bwd=2 * one, total=3 * one)
         if c.chain_1d:
             M, H, F = c.dims
             one = 2.0 * M * H * (F // c.grid.p)

@@ -20,13 +20,3 @@ def pytest_collection_modifyitems(config, items):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
-
-
-@pytest.fixture(scope="session", autouse=True)
-def _kernel_variant_from_env():
-    """TP_TEST_VARIANT=<n> runs the whole session with kernel variant n (tuning knob 4)."""
-    v = os.environ.get("TP_TEST_VARIANT")
-    if v:
-        import paper_2110_14883_amd as T
-        T.tp_plan_override(4, int(v))
-    yield

@@ -203,3 +203,24 @@ def test_workspace_size_bounds():
             assert ws <= 8 * mp["m"] * mp["n"] * 4
     # a share with one output tile and a long contraction must split K
     assert T.tp_linear_workspace_size(T.Grid(T.MODE_2D, q=1), (256, 65536, 256), 0) > 0
+
+
+def test_range_test_stored_bytes():
+    """The byte count of the two-layer range test: a hand count for one grid, and the ordering the
+    paper's memory experiment reports (Section 4, Memory Efficiency: 2D / 2.5D / 3D below 1D, 3D lowest
+    at 8 GPUs, the gap widening with depth)."""
+    from paper_2110_14883_amd import range_test as R
+    M, h = 1024, 256
+    g2 = T.Grid(T.MODE_2D, q=2)
+    blk, w = (M // 2) * (h // 2), (h // 2) ** 2
+    assert R.stored_bytes(g2, M, h) == 7 * 2 * blk + 2 * 2 * w + 2 * 2 * (h // 2) + 2 * 4 * w
+    assert R.stored_bytes(T.Grid(T.MODE_2P5D, q=2, d=1), M, h) == R.stored_bytes(g2, M, h)
+    g1 = T.Grid(T.MODE_1D_COL, p=4)
+    assert R.stored_bytes(g1, M, h) == 2 * M * h * 2 + 4 * M * h * 2 + 3 * 2 * M * h // 4 + (2 + 4) * 2 * h * h // 4 + 2 * h // 4 + 2 * h
+    for batch, hidden in ((64, 2048), (512, 2048), (32, 16384)):
+        for n in (4, 8):
+            sizes = [R.stored_bytes(g, batch * R.SEQ, hidden) for _, g in R.grids(n)]
+            assert sizes[0] > sizes[1] >= sizes[2]
+    # hidden 16384 on 8 GPUs: the paper measures 62 % (2.5D) and 74.2 % (3D) below 1D; the chunk count gives the same picture
+    s1, s25, s3 = [R.stored_bytes(g, 32 * R.SEQ, 16384) for _, g in R.grids(8)]
+    assert 0.55 < 1 - s25 / s1 < 0.75 and 0.70 < 1 - s3 / s1 < 0.85
