@@ -59,6 +59,14 @@ def test_k_rotation_off_and_other_group_heights():
             run_share(grid, dims, backward=False, label=f"group height {group}")
 
 
+def test_many_tiles_per_workgroup():
+    """More tiles than workgroups (128 x 128 tiles forced: 324 per product on 256 persistent
+    workgroups): all three memory forms, one-step and two-step shares, ragged edges."""
+    with overrides(tile=4):
+        run_share(T.Grid(T.MODE_2D, q=1), (2250, 2184, 2312), use_own_slot=False, label="324 tiles per product")
+        run_share(T.Grid(T.MODE_2D, q=2, ri=1, rj=0), (2 * 2250, 2 * 520, 2 * 2312), backward=False, y_dtype="f32", label="two steps")
+
+
 def test_prefix_of_steps_and_bias_only():
     grid, dims = T.Grid(T.MODE_3D, p=2, ri=1, rj=1, rk=0), (4 * 96, 2 * 128, 2 * 256)
     run_share(grid, dims, n_steps=1, label="3d literal single step")
@@ -71,6 +79,39 @@ def test_degenerate_extents():
     run_share(T.Grid(T.MODE_2D, q=1), (1, 8, 8), y_dtype="f32", dx_dtype="f32", label="1x8x8")
     run_share(T.Grid(T.MODE_2D, q=2, ri=1, rj=1), (2, 16, 16), label="q2 of 2x16x16")
     run_share(T.Grid(T.MODE_1D_COL, p=1), (257, 72, 8), y_dtype="f32", label="257x72x8")
+
+
+def test_largest_leading_dimension_and_many_rows():
+    """Blocks that are narrow views of very wide arrays (ld = 2^21 elements, the largest the library
+    takes: every in-tile byte offset still fits 31 bits) and a share with millions of ragged rows."""
+    m, k, n = 300, 136, 72
+    ld = 1 << 21
+    x_bits = S.normal_block_bf16(21, S.T_X, k, 0, m, 0, k, 1.0)
+    w_bits = S.normal_block_bf16(21, S.T_W1, n, 0, k, 0, n, 0.02)
+    g_bits = S.normal_block_bf16(21, S.T_G, n, 0, m, 0, n, 1.0)
+    wide_x = torch.zeros((m, ld), dtype=torch.bfloat16, device="cuda")
+    wide_g = torch.zeros((m, ld), dtype=torch.bfloat16, device="cuda")
+    wide_y = torch.zeros((m, ld), dtype=torch.float32, device="cuda")
+    xv, gv, yv = wide_x[:, ld - k:], wide_g[:, 8:8 + n], wide_y[:, ld - n:]
+    xv.copy_(dev(x_bits)); gv.copy_(dev(g_bits))
+    w = dev(w_bits)
+    grid, dims = T.Grid(T.MODE_2D, q=1), (m, k, n)
+    T.tp_linear_fwd(grid, dims, 1, [xv], [w], None, T.EPI_NONE, yv, None, None)
+    dx = torch.empty((m, k), dtype=torch.float32, device="cuda")
+    dw = torch.empty((k, n), dtype=torch.float32, device="cuda")
+    T.tp_linear_bwd(grid, dims, 1, 1, da_row_blocks=[gv], w_blocks_dx=[w], x_blocks_dw=[xv], da_col_blocks=[gv], dx=dx, dw=dw)
+    torch.cuda.synchronize()
+    x64, w64, g64 = f64(x_bits), f64(w_bits), f64(g_bits)
+    check(host64(yv), x64 @ w64, "f32", "Y through ld = 2^21 views")
+    check(host64(dx), O.share_dx([g64], [w64]), "f32", "dX, dA read through an ld = 2^21 view")
+    check(host64(dw), O.share_dw([x64], [g64]), "f32", "dW, both operands through ld = 2^21 views")
+    assert float(wide_y[:, :ld - n].abs().max()) == 0.0
+    del wide_x, wide_g, wide_y
+    with pytest.raises(T.TpError) as e:
+        T.tp_linear_fwd(grid, dims, 1, [(xv.data_ptr(), 2 * ld)], [w], None, T.EPI_NONE, yv, None, None)
+    assert e.value.status == 4
+    # 3,000,003 token rows (11,719 tile rows, the last with 3 rows), narrow layer
+    run_share(T.Grid(T.MODE_1D_COL, p=1), (3_000_003, 8, 16), y_dtype="f32", dx_dtype="f32", label="3M ragged rows")
 
 
 def test_gelu_tails_and_strided_blocks():

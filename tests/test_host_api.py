@@ -129,6 +129,10 @@ def test_grid_and_shape_errors():
     assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_2D, q=32), (64, 64, 64), 0)) == 3  # more steps than TP_MAX_STEPS
     assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_1D_COL, p=3), d, 0)) == 4
     assert T.tp_linear_workspace_size(T.Grid(T.MODE_2D, q=2, ri=5), d, 0) == 0
+    # empty layers are rejected, not treated as no-ops
+    for empty in ((0, 64, 64), (64, 0, 64), (64, 64, 0), (-8, 64, 64)):
+        assert _st(lambda: T.tp_block_map(T.Grid(T.MODE_2D, q=1), empty, 0)) == 4
+        assert T.tp_linear_workspace_size(T.Grid(T.MODE_2D, q=1), empty, 0) == 0
 
 
 def test_argument_errors_before_any_launch():
