@@ -19,7 +19,7 @@ the unpartitioned layer, so the ground truth is the plain definition
 
 in fp64, and a rank's share is a block (or an additive partial) of it, picked
 by the partition map below.  Conventions (the paper fixes none of them; they
-are this build's readings, listed in the design notes): tokens are rows,
+are this build's readings): tokens are rows,
 X:[M,H], W:[H,F] (in x out), b:[F]; the step index k runs upward; erf-GeLU.
 
 Rounding points: where a bf16 tensor is handed from one product to the next
