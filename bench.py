@@ -6,8 +6,9 @@
 A step is one pass of the whole hot path of one rank's share (forward and backward, every
 product and elementwise kernel) over one batch of seeded synthetic blocks that are already
 resident in HBM.  The headline workload is the 1D (size 4) feed-forward share, M=16384, H=4096,
-F=16384 (six 16384 x 4096 x 4096 products); the other configurations are measured after it with
-fewer steps and reported under "per_config".  Prints ONE JSON line.
+F=16384 (six 16384 x 4096 x 4096 products); the other configurations are measured after it, each
+for a length chosen from its step time (>= 80 ms of warm-up, >= 250 ms timed: shorter runs sit in
+the power controller's settling transient), and reported under "per_config".  Prints ONE JSON line.
 
 value       = GEMM flops of the step / wall time of the step (bf16 TFLOP/s, fp32 accumulation)
 roofline    = the dominant kernel (largest share of step time): its flops per launch / its average
@@ -55,12 +56,13 @@ def gemm_symbol(form: str, epi: int, f32_out: bool) -> str:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", default="c2_1d_n4_mlp")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--extra-steps", type=int, default=20)
+    ap.add_argument("--extra-steps", type=int, default=0,
+                    help="timed steps of each other configuration (0 = automatic: >= 80 ms of warm-up, >= 250 ms timed)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU's share of the tensor-parallel layer; the blocks other "
@@ -259,8 +261,25 @@ def main() -> int:
         t0 = time.time()
         builder = {"partials": build_partials, "gathered": build_gathered}.get(cfg.variant) or (build_mlp1d if cfg.chain_1d else build_share)
         sets, flops = builder(cfg)
-        log(f"[bench] {cfg.name}: inputs ready in {time.time() - t0:.1f}s; warmup {warmup}, steps {steps}")
         ncall = len(sets[0])
+        if steps <= 0:
+            # Automatic length.  After a burst of work starts, the chip's power control first lets the clocks
+            # run high, then cuts them hard and takes some tens of milliseconds to settle (seen in the kernel
+            # trace: 249 us, then 376 us, then a slow return to ~255 us for the same launch).  A short workload
+            # timed over 20 steps sits inside that dip, so warm up for >= 80 ms and time >= 250 ms.
+            for i in range(3):
+                for _, _, _, fn in sets[i % NSETS]:
+                    fn()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for i in range(3):
+                for _, _, _, fn in sets[i % NSETS]:
+                    fn()
+            torch.cuda.synchronize()
+            est_ms = max((time.perf_counter() - t1) * 1e3 / 3, 1e-3)
+            warmup = max(5, min(2000, int(80.0 / est_ms) + 1))
+            steps = max(20, min(4000, int(250.0 / est_ms) + 1))
+        log(f"[bench] {cfg.name}: inputs ready in {time.time() - t0:.1f}s; warmup {warmup}, steps {steps}")
         for i in range(warmup):
             for _, _, _, fn in sets[i % NSETS]:
                 fn()
@@ -284,7 +303,7 @@ def main() -> int:
                                  tflops=round(fl / ms / 1e9, 1) if fl else None))
         res = dict(workload=cfg.name, note=cfg.note, ms_per_step=round(ms_step, 4), gemm_flops=flops,
                    tflops=round(flops / ms_step / 1e9, 1), pct_of_peak=round(flops / ms_step / 1e9 / PEAK_BF16_TFLOPS * 100, 2),
-                   calls=per_call)
+                   steps=steps, warmup=warmup, calls=per_call)
         del sets
         torch.cuda.empty_cache()
         return res

@@ -153,10 +153,24 @@ def run_point(name: str, grid: B.Grid, batch: int, h: int, iters: int) -> dict:
     calls, flops = build_share(grid, M, h, gen)
     torch.cuda.synchronize()
     resident = torch.cuda.memory_allocated() - base           # live buffers of the step (set-up temporaries are gone)
+    import time
     for _ in range(3):
         for fn in calls:
             fn()
     torch.cuda.synchronize()
+    if iters <= 0:
+        # length from the step time: >= 80 ms of warm-up and >= 200 ms timed, so that the point is not
+        # measured inside the power controller's settling transient after the buffers were filled
+        t0 = time.perf_counter()
+        for _ in range(3):
+            for fn in calls:
+                fn()
+        torch.cuda.synchronize()
+        est_ms = max((time.perf_counter() - t0) * 1e3 / 3, 1e-3)
+        for _ in range(min(2000, int(80.0 / est_ms) + 1)):
+            for fn in calls:
+                fn()
+        iters = max(10, min(4000, int(200.0 / est_ms) + 1))
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(iters):
@@ -167,13 +181,14 @@ def run_point(name: str, grid: B.Grid, batch: int, h: int, iters: int) -> dict:
     ms = e0.elapsed_time(e1) / iters
     del calls
     return dict(scheme=name, batch=batch, hidden=h, tokens=M, stored_bytes=stored_bytes(grid, M, h),
-                resident_bytes=int(resident), gemm_flops=flops, ms_per_step=round(ms, 4), tflops=round(flops / ms / 1e9, 1))
+                resident_bytes=int(resident), gemm_flops=flops, ms_per_step=round(ms, 4), iters=iters,
+                tflops=round(flops / ms / 1e9, 1))
 
 
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
     ap.add_argument("--quick", action="store_true", help="two points per sweep instead of four")
-    ap.add_argument("--iters", type=int, default=10)
+    ap.add_argument("--iters", type=int, default=0, help="timed steps per point (0 = automatic, from the step time)")
     args = ap.parse_args(argv)
     import torch
     assert torch.cuda.is_available(), "the range test needs the GPU"
@@ -181,7 +196,7 @@ def main(argv=None) -> int:
     batches = [64, 512] if args.quick else [64, 128, 256, 512]
     hiddens = [2048, 16384] if args.quick else [2048, 4096, 8192, 16384]
     # warm the clocks: the first launches of a process run slower
-    warm = run_point("warm-up", grids(4)[1][1], 32, 2048, 20)
+    warm = run_point("warm-up", grids(4)[1][1], 32, 2048, 200)
     print(f"# warm-up {warm['tflops']} TFLOP/s", file=sys.stderr, flush=True)
     rows = []
     for n_gpus in (4, 8):
