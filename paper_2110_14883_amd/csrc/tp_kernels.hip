@@ -249,20 +249,41 @@ __device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const in
     Stage st;
     // Inside a step the K tiles are taken in a rotated order that differs from C tile to C tile, so
     // that the CUs of one XCD are not all asking the same memory channel for the same K offset.
-    auto fetch = [&](const TileCoord& c, int tile) __attribute__((always_inline)) {
-        const int st_ = tile / KT;
-        int kt = tile - st_ * KT + c.rot;
+    // Operand stream of this wave group.  The K tiles of a C tile are fetched strictly in order (units
+    // z, z+Z, z+2Z, ... of the n_steps x KT sequence), so the step a fetch belongs to is tracked
+    // incrementally: the operand block's pointer and leading dimension are re-read from the argument
+    // block only when the step changes, and nothing is divided inside the K loop.
+    int f_step = 0, f_kt = 0;                     // step (operand slot) and K tile inside it, before the rotation
+    const uint16_t* f_ptr = nullptr;
+    int f_ld = 0;
+    auto open_step = [&](int s) __attribute__((always_inline)) {
+        f_step = s;
+        if constexpr (IS_P) { f_ptr = static_cast<const uint16_t*>(p.a[s]); f_ld = p.lda[s]; }
+        else                { f_ptr = static_cast<const uint16_t*>(p.b[s]); f_ld = p.ldb[s]; }
+    };
+    auto seek = [&](const TileCoord& c, int unit) __attribute__((always_inline)) {
+        const int s = unit / KT;
+        f_kt = unit - s * KT;
+        open_step(s + c.g);                       // a grouped launch has one step per group: operand slot = group
+    };
+    auto fetch_next = [&](const TileCoord& c) __attribute__((always_inline)) {
+        int kt = f_kt + c.rot;
         if (kt >= KT) kt -= KT;
         const int k0 = kt * BK;
-        const int s = st_ + c.g;             // a grouped launch has one step per group: operand slot = group
+        // (the leading dimension is made opaque here: seen as loop-invariant, the per-lane row offsets
+        // of all eight loads would be kept in registers across the K loop, which does not have them)
+        asm volatile("" : "+s"(f_ld));
         if constexpr (IS_P) {
-            const uint16_t* ap = static_cast<const uint16_t*>(p.a[s]);
-            if constexpr (A_KC) st.load(ap, p.lda[s], p.M, c.m0, p.K, k0, tg);
-            else                st.load(ap, p.lda[s], p.K, k0, p.M, c.m0, tg);
+            if constexpr (A_KC) st.load(f_ptr, f_ld, p.M, c.m0, p.K, k0, tg);
+            else                st.load(f_ptr, f_ld, p.K, k0, p.M, c.m0, tg);
         } else {
-            const uint16_t* bp = static_cast<const uint16_t*>(p.b[s]);
-            if constexpr (B_KC) st.load(bp, p.ldb[s], p.N, c.n0, p.K, k0, tg);
-            else                st.load(bp, p.ldb[s], p.K, k0, p.N, c.n0, tg);
+            if constexpr (B_KC) st.load(f_ptr, f_ld, p.N, c.n0, p.K, k0, tg);
+            else                st.load(f_ptr, f_ld, p.K, k0, p.N, c.n0, tg);
+        }
+        f_kt += Z;
+        while (f_kt >= KT && f_step + 1 < TP_MAX_STEPS) {      // (past the last step only after the tile's last fetch)
+            f_kt -= KT;
+            open_step(f_step + 1);
         }
     };
     auto locate = [&](int v) __attribute__((always_inline)) {
@@ -321,7 +342,8 @@ __device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const in
     int v = blockIdx.x;
     if (v >= total) return;
     TileCoord cur_tile = locate(v);
-    fetch(cur_tile, cur_tile.z);
+    seek(cur_tile, cur_tile.z);
+    fetch_next(cur_tile);
 
     while (true) {
         const int z = cur_tile.z;
@@ -335,7 +357,7 @@ __device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const in
 
         // K tile 0 -> LDS stage 0, K tile 1 -> registers
         st.store(lds + PART, tg);
-        if (my_tiles > 1) fetch(cur_tile, z + Z);
+        if (my_tiles > 1) fetch_next(cur_tile);
         __syncthreads();
 
         for (int i = 0; i < my_tiles; ++i) {
@@ -344,10 +366,10 @@ __device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const in
             if constexpr (IS_P) {
                 compute(cur);
                 if (i + 1 < my_tiles) st.store(refill, tg);
-                if (i + 2 < my_tiles) fetch(cur_tile, z + (i + 2) * Z);
+                if (i + 2 < my_tiles) fetch_next(cur_tile);
             } else {
                 if (i + 1 < my_tiles) st.store(refill, tg);
-                if (i + 2 < my_tiles) fetch(cur_tile, z + (i + 2) * Z);
+                if (i + 2 < my_tiles) fetch_next(cur_tile);
                 compute(cur);
             }
             __syncthreads();
@@ -457,7 +479,8 @@ __device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const in
         v += gridDim.x;
         if (v >= total) break;
         cur_tile = locate(v);
-        fetch(cur_tile, cur_tile.z);
+        seek(cur_tile, cur_tile.z);
+        fetch_next(cur_tile);
     }
 }
 
