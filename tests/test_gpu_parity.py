@@ -67,6 +67,35 @@ def test_many_tiles_per_workgroup():
         run_share(T.Grid(T.MODE_2D, q=2, ri=1, rj=0), (2 * 2250, 2 * 520, 2 * 2312), backward=False, y_dtype="f32", label="two steps")
 
 
+def test_seeded_random_shapes_and_grids():
+    """Forty seeded draws of (mode, grid, rank, ragged extents, output dtypes, plan overrides): every
+    element of forward and backward against the oracle.  Extents span one to a few tiles with odd tails."""
+    rng = np.random.default_rng(20211014)
+    for case in range(40):
+        mode = [T.MODE_1D_COL, T.MODE_1D_ROW, T.MODE_2D, T.MODE_2P5D, T.MODE_3D][case % 5]
+        q, d, p = 1, 1, 1
+        if mode in (T.MODE_1D_COL, T.MODE_1D_ROW):
+            p = int(rng.integers(1, 5)); rank = (int(rng.integers(0, p)), 0, 0); rc, kc, cc = (1, 1, p) if mode == T.MODE_1D_COL else (1, p, 1)
+        elif mode == T.MODE_2D:
+            q = int(rng.integers(1, 4)); rank = (int(rng.integers(0, q)), int(rng.integers(0, q)), 0); rc = kc = cc = q
+        elif mode == T.MODE_2P5D:
+            q, d = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+            rank = (int(rng.integers(0, q)), int(rng.integers(0, q)), int(rng.integers(0, d))); rc, kc, cc = q * d, q, q
+        else:
+            p = int(rng.integers(1, 3)); rank = tuple(int(rng.integers(0, p)) for _ in range(3)); rc, kc, cc = p * p, p, p
+        mb = int(rng.integers(1, 420))                       # local rows: any value
+        hb = 8 * int(rng.integers(1, 50))                    # local column extents: multiples of 8
+        fb = 8 * int(rng.integers(1, 50))
+        grid = T.Grid(mode, q=q, d=d, p=p, ri=rank[0], rj=rank[1], rk=rank[2])
+        dims = (mb * rc, hb * kc, fb * cc)
+        kw = dict(y_dtype=["bf16", "f32"][int(rng.integers(0, 2))], dx_dtype=["bf16", "f32"][int(rng.integers(0, 2))],
+                  want_db=bool(rng.integers(0, 2)), use_own_slot=bool(rng.integers(0, 2)))
+        if mode == T.MODE_1D_ROW:
+            kw.update(epi=T.EPI_NONE, backward=False, y_dtype="f32")      # the row-cut product is a partial sum: no epilogue
+        with overrides(tile=int(rng.integers(0, 5)), split=int(rng.integers(0, 4))):
+            run_share(grid, dims, label=f"draw {case}", **kw)
+
+
 def test_prefix_of_steps_and_bias_only():
     grid, dims = T.Grid(T.MODE_3D, p=2, ri=1, rj=1, rk=0), (4 * 96, 2 * 128, 2 * 256)
     run_share(grid, dims, n_steps=1, label="3d literal single step")
