@@ -219,7 +219,9 @@ int tp_mfma_probe(void* scratch, size_t scratch_bytes, int iters, double* flops,
  * tp_plan_override -- tuning hook for benchmarks and tests.  key 0: macro-tile id (0 = automatic,
  * 1 = 256x256, 2 = 128x256, 3 = 256x128, 4 = 128x128); key 1: split-K factor (0 = automatic, 1..8);
  * key 2: tile-order group height in tile rows (0 = automatic, 1..64); key 3: rotate the K-tile
- * order inside a step from tile to tile (1 = on, the default; 0 = off).  Process-wide; affects
+ * order inside a step from tile to tile (1 = on, the default; 0 = off); key 4: tail trimming (1 = on,
+ * the default: when the tiles are a little more than a whole number of rounds of the persistent
+ * workgroups, the last tile rows run as a second, smaller launch; 0 = off).  Process-wide; affects
  * later calls.  Returns TP_ERR_MODE for an unknown key or value.
  */
 int tp_plan_override(int key, int value);

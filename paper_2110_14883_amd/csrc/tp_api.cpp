@@ -15,7 +15,7 @@ namespace {
 constexpr int kCUs = 256;                       // MI355X compute units
 constexpr int64_t kMaxLd = (int64_t)1 << 21;    // keeps every in-tile byte offset below 2^31
 
-std::atomic<int> g_tile_override{0}, g_split_override{0}, g_group_override{0}, g_rotate{1};
+std::atomic<int> g_tile_override{0}, g_split_override{0}, g_group_override{0}, g_rotate{1}, g_trim{1};
 
 struct Chunks { int rc, kc, cc; };              // row chunks of X/Y, col chunks of X (= row chunks of W), col chunks of W/Y
 
@@ -126,13 +126,21 @@ int build_partials(const tp_grid_t* g, const tp_dims_t* d, int pass, PartialsSha
     return TP_OK;
 }
 
-struct Plan { int tile_id, bm, bn, tiles_m, tiles_n, split_k, group_m, groups; };
+struct Plan {
+    int tile_id, bm, bn, tiles_m, tiles_n, split_k, group_m, groups;
+    // Tail trimming: when the tile count is a little more than a whole number of rounds of the 256
+    // persistent workgroups, the last tile rows are cut off and run as a second, small launch with a
+    // plan of their own, so that the main launch ends on a full round.  m_main = rows of the main launch
+    // (0 = not trimmed); the tail covers rows [m_main, m).
+    int64_t m_main;
+    int tail_tile_id, tail_tiles_m, tail_tiles_n, tail_split;
+};
 
 // Pick the macro-tile and the split of K so that the launch fills whole waves of the 256 CUs.
 // Cost model: (waves of workgroups) x (K tiles per workgroup) x (tile area), plus the fp32
 // round trip of the partials when K is split.
 // groups > 1: that many products of the same extents share one launch (tiles_m, tiles_n stay per product).
-Plan make_plan(int64_t m, int64_t n, int64_t k, int n_steps, int groups = 1) {
+Plan plan_whole(int64_t m, int64_t n, int64_t k, int n_steps, int groups, double* cost_out) {
     const int64_t T = (int64_t)n_steps * ((k + 63) / 64);
     Plan best{};
     double best_cost = 1e300;
@@ -160,15 +168,52 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int n_steps, int groups = 1) {
             const double cost = main_cost + fix;
             if (cost < best_cost) {
                 best_cost = cost;
-                best = Plan{tile_ids[ti], bm, bn, (int)tm, (int)tn, z, 4, groups};
+                best = Plan{tile_ids[ti], bm, bn, (int)tm, (int)tn, z, 4, groups, 0, 0, 0, 0, 0};
             }
         }
     }
     if (best.tile_id == 0) {           // overrides left nothing admissible: fall back to the safe default
-        best = Plan{TILE_256x256, 256, 256, (int)((m + 255) / 256), (int)((n + 255) / 256), 1, 4, groups};
+        best = Plan{TILE_256x256, 256, 256, (int)((m + 255) / 256), (int)((n + 255) / 256), 1, 4, groups, 0, 0, 0, 0, 0};
     }
     const int go = g_group_override.load();
     best.group_m = go > 0 ? go : 4;
+    if (cost_out) *cost_out = best_cost;
+    return best;
+}
+
+// cycles of one C tile of the given shape over T K tiles (the cost model's unit, see plan_whole)
+double tile_cost(int bm, int bn, int64_t T) {
+    const double penalty = (bm == 256 && bn == 256) ? 1.0 : (bm == 128 && bn == 128 ? 1.65 : 1.3);
+    return (double)T * ((double)bm * bn * 64 * 2 / 4096.0 / 0.6 * penalty) + 20000.0;
+}
+
+Plan make_plan(int64_t m, int64_t n, int64_t k, int n_steps, int groups = 1) {
+    double whole_cost = 0.0;
+    Plan best = plan_whole(m, n, k, n_steps, groups, &whole_cost);
+    if (groups != 1 || !g_trim.load() || g_split_override.load() > 1) return best;
+    const int64_t T = (int64_t)n_steps * ((k + 63) / 64);
+    const int tile_ids[4] = {TILE_256x256, TILE_128x256, TILE_256x128, TILE_128x128};
+    const int forced_tile = g_tile_override.load();
+    double best_cost = whole_cost;
+    for (int ti = 0; ti < 4; ++ti) {
+        if (forced_tile && tile_ids[ti] != forced_tile) continue;
+        int bm, bn;
+        tile_shape(tile_ids[ti], &bm, &bn);
+        const int64_t tm = (m + bm - 1) / bm, tn = (n + bn - 1) / bn;
+        const int64_t tiles = tm * tn, rem = tiles % kCUs;
+        if (tiles <= kCUs || rem == 0 || rem % tn != 0) continue;      // the tail must be whole tile rows
+        const int64_t tail_rows_tiles = rem / tn;
+        if (tail_rows_tiles >= tm) continue;
+        const int64_t m_main = (tm - tail_rows_tiles) * bm;
+        double tail_cost = 0.0;
+        const Plan tail = plan_whole(m - m_main, n, k, n_steps, 1, &tail_cost);
+        const double cost = (double)((tiles - rem) / kCUs) * tile_cost(bm, bn, T) + tail_cost + 15000.0;   // + one more launch
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = Plan{tile_ids[ti], bm, bn, (int)(tm - tail_rows_tiles), (int)tn, 1, best.group_m, 1,
+                        m_main, tail.tile_id, tail.tiles_m, tail.tiles_n, tail.split_k};
+        }
+    }
     return best;
 }
 
@@ -190,6 +235,8 @@ int check_oblk(const tp_oblk_t& b, int64_t cols, bool f32_only) {
 }
 
 size_t ws_bytes_for(const Plan& p, int64_t m, int64_t n) {
+    if (p.m_main > 0)              // the main launch never splits K; the tail may
+        return p.tail_split > 1 ? (size_t)p.tail_split * (size_t)(m - p.m_main) * (size_t)n * sizeof(float) : 0;
     return p.split_k > 1 ? (size_t)p.split_k * (size_t)p.groups * (size_t)m * (size_t)n * sizeof(float) : 0;
 }
 
@@ -197,11 +244,35 @@ struct Product {                 // one validated GEMM ready to launch
     int form; Plan plan; GemmArgs args; bool active;
 };
 
+int run_one(int form, int tile_id, int split_k, const GemmArgs& a, hipStream_t stream);
+
 int run_product(const Product& pr, void* workspace, hipStream_t stream) {
     GemmArgs a = pr.args;
     a.ws = static_cast<float*>(workspace);
-    if (launch_gemm(pr.form, pr.plan.tile_id, a, stream) != hipSuccess) return TP_ERR_HIP;
-    if (pr.plan.split_k > 1) {
+    const Plan& pl = pr.plan;
+    if (pl.m_main <= 0) return run_one(pr.form, pl.tile_id, pl.split_k, a, stream);
+    // main launch: rows [0, m_main), a whole number of rounds
+    const int64_t m = a.M, m0 = pl.m_main;
+    GemmArgs mainp = a;
+    mainp.M = (int32_t)m0;
+    if (int e = run_one(pr.form, pl.tile_id, 1, mainp, stream)) return e;
+    // tail launch: rows [m_main, m) through shifted pointers, with its own tile shape and K split
+    GemmArgs tail = a;
+    tail.M = (int32_t)(m - m0);
+    tail.tiles_m = pl.tail_tiles_m; tail.tiles_n = pl.tail_tiles_n; tail.split_k = pl.tail_split;
+    for (int k = 0; k < a.n_steps; ++k) {
+        const char* ap = static_cast<const char*>(a.a[k]);
+        tail.a[k] = pr.form == FORM_TN ? ap + m0 * 2 : ap + m0 * (int64_t)a.lda[k] * 2;    // TN: A is [k][m], else [m][k]
+    }
+    tail.out = static_cast<char*>(a.out) + m0 * a.ldo * (a.out_f32 ? 4 : 2);
+    if (a.pre) tail.pre = static_cast<char*>(a.pre) + m0 * a.ldp * 2;
+    if (a.dg) tail.dg = static_cast<const char*>(a.dg) + m0 * a.lddg * 2;
+    return run_one(pr.form, pl.tail_tile_id, pl.tail_split, tail, stream);
+}
+
+int run_one(int form, int tile_id, int split_k, const GemmArgs& a, hipStream_t stream) {
+    if (launch_gemm(form, tile_id, a, stream) != hipSuccess) return TP_ERR_HIP;
+    if (split_k > 1) {
         const int groups = a.n_groups > 1 ? a.n_groups : 1;
         const int64_t mn = (int64_t)a.M * a.N;
         for (int g = 0; g < groups; ++g) {
@@ -524,6 +595,7 @@ int tp_plan_override(int key, int value) {
         case 1: if (value < 0 || value > 8) return TP_ERR_MODE; g_split_override = value; return TP_OK;
         case 2: if (value < 0 || value > 64) return TP_ERR_MODE; g_group_override = value; return TP_OK;
         case 3: g_rotate = value != 0; return TP_OK;
+        case 4: g_trim = value != 0; return TP_OK;
         default: return TP_ERR_MODE;
     }
 }

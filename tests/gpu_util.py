@@ -83,22 +83,25 @@ _overrides_active = False
 
 
 class overrides:
-    """with overrides(tile=.., split=.., group=..): plan overrides for the calls inside."""
+    """with overrides(tile=.., split=.., group=.., trim=..): plan overrides for the calls inside."""
 
-    def __init__(self, tile=0, split=0, group=0):
+    def __init__(self, tile=0, split=0, group=0, trim=1):
         self.v = (tile, split, group)
+        self.trim = trim
 
     def __enter__(self):
         global _overrides_active
         _overrides_active = any(self.v)
         for k, v in enumerate(self.v):
             T.tp_plan_override(k, v)
+        T.tp_plan_override(4, self.trim)
 
     def __exit__(self, *a):
         global _overrides_active
         _overrides_active = False
         for k in range(3):
             T.tp_plan_override(k, 0)
+        T.tp_plan_override(4, 1)
 
 
 def torch_dtype(name):

@@ -67,6 +67,17 @@ def test_many_tiles_per_workgroup():
         run_share(T.Grid(T.MODE_2D, q=2, ri=1, rj=0), (2 * 2250, 2 * 520, 2 * 2312), backward=False, y_dtype="f32", label="two steps")
 
 
+@pytest.mark.parametrize("trim", [1, 0])
+def test_tail_rows_as_a_second_launch(trim):
+    """272 tiles of 128 x 128 on 256 workgroups: with trimming the last tile row (ragged) runs as a
+    launch of its own through shifted pointers -- forward with both outputs and dX (first case), dW
+    (second case), the 1D chain's GeLU' epilogue (third); same results with trimming off."""
+    with overrides(tile=4, trim=trim):
+        run_share(T.Grid(T.MODE_2D, q=1), (2139, 2048, 2048), use_own_slot=False, want_db=True, label=f"fwd and dX trimmed ({trim})")
+        run_share(T.Grid(T.MODE_2D, q=2, ri=0, rj=1), (2 * 1000, 2 * 2136, 2 * 2048), y_dtype="f32", label=f"dW trimmed, two steps ({trim})")
+        _mlp1d(2, 1, 2139, 2048, 2 * 2048, rows=None)
+
+
 def test_seeded_random_shapes_and_grids():
     """Forty seeded draws of (mode, grid, rank, ragged extents, output dtypes, plan overrides): every
     element of forward and backward against the oracle.  Extents span one to a few tiles with odd tails."""

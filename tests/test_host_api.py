@@ -205,6 +205,13 @@ def test_workspace_size_bounds():
             mp = T.tp_block_map(c.grid, c.dims, pass_)
             ws = T.tp_linear_workspace_size(c.grid, c.dims, pass_)
             assert ws <= 8 * mp["m"] * mp["n"] * 4
+    # trimming on or off, the bound holds
+    T.tp_plan_override(4, 0)
+    for c in WL.CONFIGS:
+        for pass_ in (0, 1, 2):
+            mp = T.tp_block_map(c.grid, c.dims, pass_)
+            assert T.tp_linear_workspace_size(c.grid, c.dims, pass_) <= 8 * mp["m"] * mp["n"] * 4
+    T.tp_plan_override(4, 1)
     # a share with one output tile and a long contraction must split K
     assert T.tp_linear_workspace_size(T.Grid(T.MODE_2D, q=1), (256, 65536, 256), 0) > 0
 
