@@ -67,6 +67,55 @@ def test_many_tiles_per_workgroup():
         run_share(T.Grid(T.MODE_2D, q=2, ri=1, rj=0), (2 * 2250, 2 * 520, 2 * 2312), backward=False, y_dtype="f32", label="two steps")
 
 
+def test_calls_can_be_captured_in_a_hip_graph():
+    """The library only enqueues kernels on the caller's stream (no allocation, no synchronisation,
+    no memset), so a whole forward + backward of a share can be captured once and replayed: every
+    replay, with eager work and synchronisations in between, reproduces the eager results bit for bit."""
+    grid, dims = T.Grid(T.MODE_2D, q=2, ri=1, rj=0), (2 * 300, 2 * 136, 2 * 328)
+    inp = WL.make_share_inputs(grid, dims)
+    m, n, k = inp["m"], inp["n"], inp["k"]
+    xs, ws_ = [dev(b) for b in inp["x_blocks"]], [dev(b) for b in inp["w_blocks"]]
+    bias, g = dev(inp["bias"]), dev(inp["g_own"])
+    wdx, xdw = [dev(b) for b in inp["w_blocks_dx"]], [dev(b) for b in inp["x_blocks_dw"]]
+    peers_x = {i: dev(p[0]) for i, p in inp["peers_dx"].items()}
+    peers_w = {i: dev(p[0]) for i, p in inp["peers_dw"].items()}
+    ws = workspace_for(grid, dims)
+    with overrides(split=2):            # include the split-K fix-up kernels in the captured work
+        need = 8 * 4 * max(m * n, m * k, k * n)
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        outs = [dict(y=torch.zeros((m, n), dtype=torch.bfloat16, device="cuda"), pre=torch.zeros((m, n), dtype=torch.bfloat16, device="cuda"),
+                     da=torch.zeros((m, n), dtype=torch.bfloat16, device="cuda"), dx=torch.zeros((m, k), dtype=torch.float32, device="cuda"),
+                     dw=torch.zeros((k, n), dtype=torch.float32, device="cuda"), db=torch.zeros((n,), dtype=torch.float32, device="cuda"))
+                for _ in range(2)]
+
+        def step(o):
+            T.tp_linear_fwd(grid, dims, 2, xs, ws_, bias, T.EPI_BIAS_GELU, o["y"], o["pre"], ws)
+            rows = [None if i == inp["own_slot_dx"] else peers_x[i] for i in range(2)]
+            cols = [None if i == inp["own_slot_dw"] else peers_w[i] for i in range(2)]
+            T.tp_linear_bwd(grid, dims, 2, 2, dy_own=g, preact_own=o["pre"], da_row_blocks=rows, w_blocks_dx=wdx,
+                            x_blocks_dw=xdw, da_col_blocks=cols, own_slot_dx=inp["own_slot_dx"], own_slot_dw=inp["own_slot_dw"],
+                            dx=o["dx"], dw=o["dw"], da_own_out=o["da"], db=o["db"], workspace=ws)
+
+        step(outs[0])                   # eager reference
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step(outs[1])               # warm-up on the capture stream
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step(outs[1])
+        torch.cuda.synchronize()
+        for replay in range(3):
+            for t in outs[1].values():
+                t.fill_(7.0)            # eager work between replays; also proves the replay rewrites everything
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for name in outs[0]:
+                assert torch.equal(outs[0][name], outs[1][name]), (replay, name)
+
+
 @pytest.mark.parametrize("trim", [1, 0])
 def test_tail_rows_as_a_second_launch(trim):
     """272 tiles of 128 x 128 on 256 workgroups: with trimming the last tile row (ragged) runs as a
