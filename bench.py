@@ -301,9 +301,38 @@ def main() -> int:
             ms = sum(ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(steps)) / steps
             per_call.append(dict(call=label, kernel=sym, ms=round(ms, 4), flops=fl,
                                  tflops=round(fl / ms / 1e9, 1) if fl else None))
+        graph = None
+        if ms_step < 0.2:
+            # launch-latency-bound step: also time it replayed from a HIP graph (the library only enqueues
+            # kernels, so its calls can be captured); one graph per buffer set, replayed in rotation
+            side = torch.cuda.Stream()
+            graphs = []
+            with torch.cuda.stream(side):
+                for calls in sets:
+                    for _, _, _, fn in calls:
+                        fn()
+                    side.synchronize()
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=side):
+                        for _, _, _, fn in calls:
+                            fn()
+                    graphs.append(g)
+            torch.cuda.synchronize()
+            for i in range(warmup):
+                graphs[i % NSETS].replay()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for i in range(steps):
+                graphs[i % NSETS].replay()
+            torch.cuda.synchronize()
+            g_ms = (time.perf_counter() - t1) * 1e3 / steps
+            graph = dict(ms_per_step=round(g_ms, 4), tflops=round(flops / g_ms / 1e9, 1))
+            del graphs
         res = dict(workload=cfg.name, note=cfg.note, ms_per_step=round(ms_step, 4), gemm_flops=flops,
                    tflops=round(flops / ms_step / 1e9, 1), pct_of_peak=round(flops / ms_step / 1e9 / PEAK_BF16_TFLOPS * 100, 2),
                    steps=steps, warmup=warmup, calls=per_call)
+        if graph:
+            res["hip_graph_replay"] = graph
         del sets
         torch.cuda.empty_cache()
         return res
@@ -360,6 +389,7 @@ def main() -> int:
                    "gemm_flops_per_step": main_res["gemm_flops"]},
         "pct_of_mfma_peak": main_res["pct_of_peak"],
         "roofline": roofline, "cpu_baseline": cpu, "calls": main_res["calls"], "per_config": extra,
+        "hip_graph_replay": main_res.get("hip_graph_replay"),
     }
     print(json.dumps(out), flush=True)
     return 0
