@@ -34,11 +34,11 @@ NSETS = int(os.environ.get("TPL_BENCH_NSETS", "3"))   # buffer sets rotated thro
 # HBM-side bytes per launch (read + written) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/gemm_256x256_config2_1d_mlp.md (scaled there by a copy of known size).
 MEASURED_TRAFFIC_BYTES = {
-    "tpl::tp_gemm_kernel<256, 256, true, false, 2, false>": 1176373600,
-    "tpl::tp_gemm_kernel<256, 256, true, false, 0, true>": 1163482550,
-    "tpl::tp_gemm_kernel<256, 256, true, true, 3, false>": 1281372085,
-    "tpl::tp_gemm_kernel<256, 256, true, true, 0, true>": 1200513418,
-    "tpl::tp_gemm_kernel<256, 256, false, false, 0, true>": 892267003,
+    "tpl::tp_gemm_kernel<256, 256, true, false, 2, false>": 1169213543,
+    "tpl::tp_gemm_kernel<256, 256, true, false, 0, true>": 1173524065,
+    "tpl::tp_gemm_kernel<256, 256, true, true, 3, false>": 1245971806,
+    "tpl::tp_gemm_kernel<256, 256, true, true, 0, true>": 1193097948,
+    "tpl::tp_gemm_kernel<256, 256, false, false, 0, true>": 892205206,
 }
 
 

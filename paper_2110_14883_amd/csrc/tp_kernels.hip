@@ -383,7 +383,13 @@ __device__ __forceinline__ void gemm_role(const GemmArgs& p, char* lds, const in
         {
             const int m_sub = cur_tile.m0 + wm * (BM / 2);          // first row of this wave's slab
             const int n_sub = cur_tile.n0 + wn * (BN / 4);          // first column
-            const int r = l & 31;                                   // row of this lane inside a 32-row slab
+            // (lane-derived values of the epilogue are formed here, from an opaque copy of the lane id, so
+            // that none of them is computed ahead of the K loop and carried across it in a register)
+            int le = l;
+            asm volatile("" : "+v"(le));
+            const int r = le & 31;                                  // row of this lane inside a 32-row slab
+            const int ch = le >> 5;                                 // which half of each 8-column group this lane holds
+            const int l = le;
             const bool partial = Z > 1;          // split K: raw fp32 partials, the fix-up kernel runs the epilogue
             constexpr bool use_bias = EPI == EPI_BIAS || EPI == EPI_BIAS_GELU;
             constexpr bool use_gelu = EPI == EPI_BIAS_GELU;
