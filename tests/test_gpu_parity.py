@@ -67,6 +67,44 @@ def test_many_tiles_per_workgroup():
         run_share(T.Grid(T.MODE_2D, q=2, ri=1, rj=0), (2 * 2250, 2 * 520, 2 * 2312), backward=False, y_dtype="f32", label="two steps")
 
 
+@pytest.mark.parametrize("name,grid,ogrid,dims", [
+    ("2d_q2", T.Grid(T.MODE_2D, q=2, ri=1, rj=0), O.Grid(O.MODE_2D, q=2, ri=1, rj=0), (2 * 300, 2 * 136, 2 * 328)),
+    ("3d_p2", T.Grid(T.MODE_3D, p=2, ri=1, rj=0, rk=1), O.Grid(O.MODE_3D, p=2, ri=1, rj=0, rk=1), (4 * 150, 2 * 136, 2 * 264)),
+])
+def test_chained_forward_then_backward_end_to_end(name, grid, ogrid, dims):
+    """Forward on the GPU, then backward fed with the GPU's OWN saved pre-activation (not the oracle's):
+    the stage errors may compound, so the results are held to the bf16 tolerance against the
+    oracle's unbroken fp64 chain."""
+    inp = WL.make_share_inputs(grid, dims)
+    m, n, k, S_ = inp["m"], inp["n"], inp["k"], inp["n_steps_fwd"]
+    ws = workspace_for(grid, dims)
+    y = torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
+    pre = torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
+    T.tp_linear_fwd(grid, dims, S_, [dev(b) for b in inp["x_blocks"]], [dev(b) for b in inp["w_blocks"]], dev(inp["bias"]),
+                    T.EPI_BIAS_GELU, y, pre, ws)
+    sx, sw = inp["n_steps_dx"], inp["n_steps_dw"]
+    peer = lambda pair: dev(O.f64_to_bf16_bits(O.share_da(f64(pair[0]), f64(pair[1]))))
+    rows = [None if i == inp["own_slot_dx"] else peer(inp["peers_dx"][i]) for i in range(sx)]
+    cols = [None if i == inp["own_slot_dw"] else peer(inp["peers_dw"][i]) for i in range(sw)]
+    dx = torch.empty((m, k), dtype=torch.float32, device="cuda")
+    dw = torch.empty((inp["dw"]["m"], inp["dw"]["n"]), dtype=torch.float32, device="cuda")
+    da = torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
+    T.tp_linear_bwd(grid, dims, sx, sw, dy_own=dev(inp["g_own"]), preact_own=pre, da_row_blocks=rows,
+                    w_blocks_dx=[dev(b) for b in inp["w_blocks_dx"]], x_blocks_dw=[dev(b) for b in inp["x_blocks_dw"]],
+                    da_col_blocks=cols, own_slot_dx=inp["own_slot_dx"], own_slot_dw=inp["own_slot_dw"],
+                    dx=dx, dw=dw, da_own_out=da, workspace=ws)
+    torch.cuda.synchronize()
+    # the oracle's own chain from the same inputs
+    A, Y = O.share_fwd([f64(b) for b in inp["x_blocks"]], [f64(b) for b in inp["w_blocks"]], f64(inp["bias"]))
+    dA_own = O.share_da(f64(inp["g_own"]), O.round_to_bf16(A))
+    da_x = [dA_own if i == inp["own_slot_dx"] else O.share_da(f64(inp["peers_dx"][i][0]), f64(inp["peers_dx"][i][1])) for i in range(sx)]
+    da_w = [dA_own if i == inp["own_slot_dw"] else O.share_da(f64(inp["peers_dw"][i][0]), f64(inp["peers_dw"][i][1])) for i in range(sw)]
+    check(host64(y), Y, "bf16", f"{name}: Y")
+    check(host64(da), dA_own, "bf16", f"{name}: dA from the GPU's own A_saved")
+    check(host64(dx), O.share_dx(da_x, [f64(b) for b in inp["w_blocks_dx"]]), "bf16", f"{name}: dX, chained")
+    check(host64(dw), O.share_dw([f64(b) for b in inp["x_blocks_dw"]], da_w), "bf16", f"{name}: dW, chained")
+
+
 def test_calls_can_be_captured_in_a_hip_graph():
     """The library only enqueues kernels on the caller's stream (no allocation, no synchronisation,
     no memset), so a whole forward + backward of a share can be captured once and replayed: every
