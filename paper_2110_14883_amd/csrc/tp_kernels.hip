@@ -23,6 +23,7 @@
 //     are 8- or 16-byte wide; the first K tile of the next C tile is already in flight while the
 //     epilogue runs;
 //   * tile ids are spread so that each XCD (own L2) works on a compact patch of tiles.
+#include <atomic>
 #include <type_traits>
 
 #include "tp_internal.h"
@@ -647,12 +648,17 @@ void tile_shape(int tile_id, int* bm, int* bn) {
 template <int BM, int BN, bool A_KC, bool B_KC, int EPI, bool F32_OUT>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
     constexpr int lds_bytes = 2 * (BM + BN) * BK * 2 + 8 * EPI_BYTES_PER_WAVE;
-    static bool attr_set = false;           // same value every time: a repeated set is harmless
-    if (!attr_set) {
+    // the LDS limit is a per-device attribute of the kernel: set it once on every device that launches
+    // it (same value every time, so a repeated or concurrent set is harmless)
+    static std::atomic<uint64_t> attr_done{0};
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (!(attr_done.load(std::memory_order_relaxed) & bit)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tp_gemm_kernel<BM, BN, A_KC, B_KC, EPI, F32_OUT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_done.fetch_or(bit, std::memory_order_relaxed);
     }
     // persistent: never more workgroups than the chip holds at once (one per CU with this much LDS)
     const int total = a.tiles_m * a.tiles_n * a.split_k;
