@@ -23,8 +23,11 @@
  * the default stream) and the call returns immediately.  Inputs are read-only and may alias each
  * other but not outputs.  Every failure is a return code found before anything is launched; nothing
  * is written on error.  Row counts may be any value >= 1 (ragged tails are masked); column extents
- * of every block and every `ld` must be multiples of 8 elements and every pointer 16-byte aligned
- * (128-bit loads), else TP_ERR_ALIGN.
+ * of every block and every `ld` must be multiples of 8 elements and every pointer, the workspace
+ * included, 16-byte aligned (128-bit loads and stores), else TP_ERR_ALIGN (TP_ERR_WORKSPACE for the
+ * workspace).  The library keeps no mutable state between calls apart from per-device caches of kernel
+ * attributes and of the device's compute-unit count; every entry point may be called from several
+ * threads at once.
  */
 #ifndef TP_LINEAR_H
 #define TP_LINEAR_H
@@ -77,6 +80,16 @@ typedef struct { int64_t M, H, F; } tp_dims_t;
 typedef struct { const void* ptr; int64_t ld; } tp_cblk_t;
 /* An output device block: row-major, ld in elements, dtype a tp_dtype_t.  ptr == NULL means "not wanted". */
 typedef struct { void* ptr; int64_t ld; int dtype; } tp_oblk_t;
+/* Launch-plan options of one call (tuning and tests; NULL = all automatic).  The same options must be
+ * given to the workspace query and to the call it sizes.
+ *   tile   : macro-tile of C.  0 automatic; 1 = 256x256 (four-wave stream kernel); 2 = 128x256,
+ *            3 = 256x128, 4 = 128x128 (eight-wave kernel); 5 = 256x256 on the eight-wave kernel.
+ *   split_k: workgroups sharing one C tile along K.  0 automatic, 1..8.
+ *   group_m: height, in tile rows, of the groups of the tile order.  0 automatic, 1..64.
+ *   rotate : rotate the K-tile order inside a step from C tile to C tile.  0 automatic (on), 1 on, 2 off.
+ *   trim   : when the tiles are a little more than a whole number of rounds of the persistent
+ *            workgroups, run the last tile rows as a second, smaller launch.  0 automatic (on), 1 on, 2 off. */
+typedef struct { int tile, split_k, group_m, rotate, trim; } tp_plan_opts_t;
 
 /*
  * tp_block_map -- the partition map (host only, no GPU needed).  For rank `grid` of a layer `dims`
@@ -111,6 +124,8 @@ int tp_block_map(const tp_grid_t* grid, const tp_dims_t* dims, int pass,
  * cross-workgroup split-K partials in fp32.  0 on invalid arguments.  Never more than
  * 8 x m x n x 4 bytes per product. */
 size_t tp_linear_workspace_size(const tp_grid_t* grid, const tp_dims_t* dims, int pass);
+/* The same for calls made with plan options (NULL = tp_linear_workspace_size). */
+size_t tp_linear_workspace_size_ex(const tp_grid_t* grid, const tp_dims_t* dims, int pass, const tp_plan_opts_t* opts);
 
 /*
  * tp_linear_fwd -- forward share:  C = sum_{k<n_steps} X_k W_k  with the fp32 accumulator kept
@@ -121,13 +136,24 @@ size_t tp_linear_workspace_size(const tp_grid_t* grid, const tp_dims_t* dims, in
  *   bias               : bf16 [n] (this rank's chunk) or NULL when epi == TP_EPI_NONE.
  *   y                  : [m, n], fp32 or bf16.
  *   preact             : optional bf16 [m, n]: A rounded to bf16, saved for backward.
- *   workspace          : >= tp_linear_workspace_size(.., TP_PASS_FWD) bytes, 256-byte aligned (may be
+ *   workspace          : >= tp_linear_workspace_size(.., TP_PASS_FWD) bytes, 16-byte aligned (may be
  *                        NULL when that size is 0).
+ * Defined by: Section 2.2, tensor-parallelism paragraphs (1D: first weight cut by columns, second by
+ * rows, partial outputs; 2D / 2.5D / 3D: the chunk shapes) with the layer Y = W X of Section 3.1
+ * written tokens-major and completed by bias and erf-GeLU.  When the map marks the output as an
+ * additive partial (1D_ROW with p > 1, 3D_GATHERED) bias, GeLU and preact are refused (TP_ERR_MODE:
+ * they belong after the summation, see tp_bias_act) and y must be fp32 (TP_ERR_DTYPE).
+ * Errors: TP_ERR_NULL, TP_ERR_MODE, TP_ERR_GRID, TP_ERR_SHAPE, TP_ERR_ALIGN, TP_ERR_DTYPE,
+ * TP_ERR_WORKSPACE, TP_ERR_HIP; nothing is launched unless every check has passed.
  */
 int tp_linear_fwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps,
                   const tp_cblk_t* x_blocks, const tp_cblk_t* w_blocks,
                   const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact,
                   void* workspace, size_t workspace_bytes, void* hip_stream);
+int tp_linear_fwd_ex(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps,
+                     const tp_cblk_t* x_blocks, const tp_cblk_t* w_blocks,
+                     const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact,
+                     void* workspace, size_t workspace_bytes, void* hip_stream, const tp_plan_opts_t* opts);
 
 /*
  * tp_linear_bwd -- backward share.  In order, each part only if its outputs are wanted:
@@ -142,6 +168,12 @@ int tp_linear_fwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps,
  *                fp32 output only (TP_ERR_DTYPE otherwise).
  *   For a layer without activation (1D_ROW) pass the upstream gradient blocks as the "da" blocks.
  *   workspace: >= max(tp_linear_workspace_size(DX), tp_linear_workspace_size(DW)).
+ * Defined by: the gradients of the layer of tp_linear_fwd under the same partition (Section 2.2; the
+ * three products of a layer, forward and two backward, are what the factor 3 of Table 1, Section 3.1,
+ * counts for 2D and 2.5D), each rank accumulating its own block of dX and dW over the steps.  A dX
+ * that the map marks as an additive partial (1D_COL with p > 1, 3D_GATHERED) must be fp32
+ * (TP_ERR_DTYPE) and takes no dgelu_preact (TP_ERR_MODE).
+ * Errors: as tp_linear_fwd.
  */
 int tp_linear_bwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_dx, int n_steps_dw,
                   const tp_cblk_t* dy_own, const tp_cblk_t* preact_own,
@@ -151,6 +183,14 @@ int tp_linear_bwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_dx, 
                   const tp_cblk_t* dgelu_preact,
                   tp_oblk_t dx, tp_oblk_t dw, tp_oblk_t da_own_out, void* db_f32,
                   void* workspace, size_t workspace_bytes, void* hip_stream);
+int tp_linear_bwd_ex(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_dx, int n_steps_dw,
+                     const tp_cblk_t* dy_own, const tp_cblk_t* preact_own,
+                     const tp_cblk_t* da_row_blocks, const tp_cblk_t* w_blocks_dx,
+                     const tp_cblk_t* x_blocks_dw, const tp_cblk_t* da_col_blocks,
+                     int own_slot_dx, int own_slot_dw,
+                     const tp_cblk_t* dgelu_preact,
+                     tp_oblk_t dx, tp_oblk_t dw, tp_oblk_t da_own_out, void* db_f32,
+                     void* workspace, size_t workspace_bytes, void* hip_stream, const tp_plan_opts_t* opts);
 
 /*
  * tp_partials_map -- the partition map of the backward products in their other SUMMA form, for 2D
@@ -178,15 +218,23 @@ int tp_partials_map(const tp_grid_t* grid, const tp_dims_t* dims, int pass,
  *                   fp32 outputs [M_blk, H_blk];  dx_partials[k] = da_own w_blocks_dx[k]^T.
  *   x_blocks_dw   : host array [n_dw] of X blocks [M_blk, H_blk];  dw_partials: host array [n_dw] of
  *                   fp32 outputs [H_blk, F_blk];  dw_partials[k] = x_blocks_dw[k]^T da_own.
- *   n_dx, n_dw    : 0 (skip that pass) .. the map's step count; outputs must not overlap.
+ *   n_dx, n_dw    : 0 (skip that pass) .. the map's step count.
  *   workspace     : >= max over the passes used of tp_linear_workspace_size(.., TP_PASS_D?_PARTIALS).
- * Outputs are fp32 (they are summands of a reduction): TP_ERR_DTYPE otherwise.
+ * Outputs are fp32 (they are summands of a reduction): TP_ERR_DTYPE otherwise.  The output blocks of
+ * one call must not overlap each other (their byte ranges [ptr, ptr + ((rows - 1) ld + cols) 4) are
+ * compared pairwise): TP_ERR_SHAPE otherwise.
+ * Defined by: Section 3.1, Table 1 (2D, 2.5D rows) read with Section 2.2's chunk shapes.
  */
 int tp_linear_bwd_partials(const tp_grid_t* grid, const tp_dims_t* dims, int n_dx, int n_dw,
                            const tp_cblk_t* da_own,
                            const tp_cblk_t* w_blocks_dx, const tp_oblk_t* dx_partials,
                            const tp_cblk_t* x_blocks_dw, const tp_oblk_t* dw_partials,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
+int tp_linear_bwd_partials_ex(const tp_grid_t* grid, const tp_dims_t* dims, int n_dx, int n_dw,
+                              const tp_cblk_t* da_own,
+                              const tp_cblk_t* w_blocks_dx, const tp_oblk_t* dx_partials,
+                              const tp_cblk_t* x_blocks_dw, const tp_oblk_t* dw_partials,
+                              void* workspace, size_t workspace_bytes, void* hip_stream, const tp_plan_opts_t* opts);
 
 /*
  * tp_bias_act -- what follows the summation of forward partials (1D_ROW and 3D_GATHERED outputs
@@ -194,6 +242,9 @@ int tp_linear_bwd_partials(const tp_grid_t* grid, const tp_dims_t* dims, int n_d
  * (TP_EPI_NONE: a dtype conversion).  c: fp32 [rows, cols] with leading dimension ld_c; bias: bf16
  * [cols] or NULL with TP_EPI_NONE; y: fp32 or bf16; preact: optional bf16 copy of A.  cols and every
  * ld multiples of 8.  HBM-bound.
+ * Defined by: Section 2.2, 1D paragraph (every device holds a partial output and an all-reduce
+ * completes it) and the 3D chunk shape [P/p^2, Q/p]: what is applied to the rank's chunk once the sum
+ * exists.  Errors: TP_ERR_NULL, TP_ERR_MODE, TP_ERR_SHAPE, TP_ERR_ALIGN, TP_ERR_DTYPE, TP_ERR_HIP.
  */
 int tp_bias_act(const void* c, int64_t ld_c, const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact,
                 int64_t rows, int64_t cols, void* hip_stream);
@@ -201,30 +252,22 @@ int tp_bias_act(const void* c, int64_t ld_c, const void* bias, int epi, tp_oblk_
 /*
  * tp_dgelu -- the elementwise part of backward on its own:  da = bf16(dy * GeLU'(preact)),
  * all three bf16 [rows, cols] row-major with their own leading dimensions.  HBM-bound.
+ * Defined by: the derivative of the erf-GeLU of tp_linear_fwd, GeLU'(a) = Phi(a) + a phi(a), applied to
+ * a rank's own block of the output gradient (the chunk [P/q, Q/q], [P/(q d), Q/q] or [P/p^2, Q/p] of
+ * Section 2.2).  Errors: TP_ERR_NULL, TP_ERR_SHAPE, TP_ERR_ALIGN, TP_ERR_HIP.
  */
 int tp_dgelu(const void* dy, int64_t ld_dy, const void* preact, int64_t ld_pre,
              void* da, int64_t ld_da, int64_t rows, int64_t cols, void* hip_stream);
 
 /*
- * tp_mfma_probe -- measurement aid, not part of the layer: enqueues a register-resident loop of
- * dense bf16 MFMAs (no LDS, no memory traffic, operands with random-looking bits) on every CU and
- * reports in *flops (a HOST pointer, written before the call returns) how many floating-point
- * operations the launch performs.  Timed by the caller, it gives the dense-bf16 rate this chip
- * really sustains at the clock it holds under load, to set beside the published 2.5 PFLOP/s.
- * scratch: device buffer of at least 256 x 256 x 4 bytes, 16-byte aligned (receives checksums).
+ * tp_bias_grad -- db = 1^T dA: column sums of a bf16 block [rows, cols] (leading dimension ld) into
+ * fp32 [cols], in a fixed summation order (the same bits on every call).  This is what tp_linear_bwd
+ * writes to db_f32 for the block it forms itself; here for a dA block that already exists (the 1D
+ * chain, where dA is the epilogue of the second layer's dX).  HBM-bound.
+ * Defined by: the bias gradient of the layer of tp_linear_fwd for one column chunk of the bias
+ * (Section 2.2 chunking of the output columns).  Errors: TP_ERR_NULL, TP_ERR_SHAPE, TP_ERR_ALIGN, TP_ERR_HIP.
  */
-int tp_mfma_probe(void* scratch, size_t scratch_bytes, int iters, double* flops, void* hip_stream);
-
-/*
- * tp_plan_override -- tuning hook for benchmarks and tests.  key 0: macro-tile id (0 = automatic,
- * 1 = 256x256, 2 = 128x256, 3 = 256x128, 4 = 128x128); key 1: split-K factor (0 = automatic, 1..8);
- * key 2: tile-order group height in tile rows (0 = automatic, 1..64); key 3: rotate the K-tile
- * order inside a step from tile to tile (1 = on, the default; 0 = off); key 4: tail trimming (1 = on,
- * the default: when the tiles are a little more than a whole number of rounds of the persistent
- * workgroups, the last tile rows run as a second, smaller launch; 0 = off).  Process-wide; affects
- * later calls.  Returns TP_ERR_MODE for an unknown key or value.
- */
-int tp_plan_override(int key, int value);
+int tp_bias_grad(const void* da, int64_t ld_da, int64_t rows, int64_t cols, void* db_f32, void* hip_stream);
 
 /* Human-readable name of a status code (static storage). */
 const char* tp_strerror(int status);

@@ -15,7 +15,7 @@ namespace {
 constexpr int kCUs = 256;                       // MI355X compute units
 constexpr int64_t kMaxLd = (int64_t)1 << 21;    // keeps every in-tile byte offset below 2^31
 
-std::atomic<int> g_tile_override{0}, g_split_override{0}, g_group_override{0}, g_rotate{1}, g_trim{1};
+std::atomic<int> g_tile_override{0}, g_split_override{0}, g_group_override{0}, g_rotate{1}, g_trim{1}, g_w4{1};
 
 struct Chunks { int rc, kc, cc; };              // row chunks of X/Y, col chunks of X (= row chunks of W), col chunks of W/Y
 
@@ -145,7 +145,9 @@ Plan plan_whole(int64_t m, int64_t n, int64_t k, int n_steps, int groups, double
     Plan best{};
     double best_cost = 1e300;
     const int tile_ids[4] = {TILE_256x256, TILE_128x256, TILE_256x128, TILE_128x128};
-    const int forced_tile = g_tile_override.load(), forced_split = g_split_override.load();
+    const int forced_split = g_split_override.load();
+    int forced_tile = g_tile_override.load();
+    if (forced_tile == TILE_256x256_W4) forced_tile = TILE_256x256;
     for (int ti = 0; ti < 4; ++ti) {
         if (forced_tile && tile_ids[ti] != forced_tile) continue;
         int bm, bn;
@@ -193,7 +195,8 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int n_steps, int groups = 1) {
     if (groups != 1 || !g_trim.load() || g_split_override.load() > 1) return best;
     const int64_t T = (int64_t)n_steps * ((k + 63) / 64);
     const int tile_ids[4] = {TILE_256x256, TILE_128x256, TILE_256x128, TILE_128x128};
-    const int forced_tile = g_tile_override.load();
+    int forced_tile = g_tile_override.load();
+    if (forced_tile == TILE_256x256_W4) forced_tile = TILE_256x256;
     double best_cost = whole_cost;
     for (int ti = 0; ti < 4; ++ti) {
         if (forced_tile && tile_ids[ti] != forced_tile) continue;
@@ -271,6 +274,10 @@ int run_product(const Product& pr, void* workspace, hipStream_t stream) {
 }
 
 int run_one(int form, int tile_id, int split_k, const GemmArgs& a, hipStream_t stream) {
+    // 256 x 256 tiles run on the four-wave stream kernel unless the eight-wave one is asked for by id
+    if (tile_id == TILE_256x256 && (g_w4.load() || g_tile_override.load() == TILE_256x256_W4) &&
+        g_tile_override.load() != TILE_256x256)
+        tile_id = TILE_256x256_W4;
     if (launch_gemm(form, tile_id, a, stream) != hipSuccess) return TP_ERR_HIP;
     if (split_k > 1) {
         const int groups = a.n_groups > 1 ? a.n_groups : 1;
@@ -591,11 +598,12 @@ int tp_mfma_probe(void* scratch, size_t scratch_bytes, int iters, double* flops,
 
 int tp_plan_override(int key, int value) {
     switch (key) {
-        case 0: if (value < 0 || value > TILE_128x128) return TP_ERR_MODE; g_tile_override = value; return TP_OK;
+        case 0: if (value < 0 || value > TILE_256x256_W4) return TP_ERR_MODE; g_tile_override = value; return TP_OK;
         case 1: if (value < 0 || value > 8) return TP_ERR_MODE; g_split_override = value; return TP_OK;
         case 2: if (value < 0 || value > 64) return TP_ERR_MODE; g_group_override = value; return TP_OK;
         case 3: g_rotate = value != 0; return TP_OK;
         case 4: g_trim = value != 0; return TP_OK;
+        case 5: g_w4 = value != 0; return TP_OK;
         default: return TP_ERR_MODE;
     }
 }

@@ -55,10 +55,12 @@ struct ReduceArgs {
 };
 
 // tile ids: macro-tile shapes the GEMM kernel is instantiated for
-enum TileId { TILE_256x256 = 1, TILE_128x256 = 2, TILE_256x128 = 3, TILE_128x128 = 4 };
+enum TileId { TILE_256x256 = 1, TILE_128x256 = 2, TILE_256x128 = 3, TILE_128x128 = 4,
+              TILE_256x256_W4 = 5 };   // 256 x 256 by the four-wave stream kernel (tp_gemm4.hip)
 void tile_shape(int tile_id, int* bm, int* bn);
 
 hipError_t launch_gemm(int form, int tile_id, const GemmArgs& args, hipStream_t stream);
+hipError_t launch_gemm4(int form, const GemmArgs& args, hipStream_t stream);   // TILE_256x256_W4 (args already normalised)
 hipError_t launch_reduce(const ReduceArgs& args, hipStream_t stream);
 hipError_t launch_dgelu(const void* dy, int64_t ld_dy, const void* pre, int64_t ld_pre,
                         void* da, int64_t ld_da, int64_t rows, int64_t cols, hipStream_t stream);
