@@ -338,13 +338,21 @@ def main() -> int:
         return res
 
     def mfma_only_ceiling():
-        """Dense bf16 MFMA rate the chip sustains with nothing else running (register-resident loop)."""
+        """Dense bf16 MFMA rate the chip sustains with nothing else running (register-resident loop of
+        libtpprobe.so, a measurement aid built beside the library, not part of it)."""
+        import ctypes as C
+        probe = C.CDLL(os.path.join(ROOT, "paper_2110_14883_amd", "libtpprobe.so"))
+        probe.tp_mfma_probe.restype = C.c_int
+        probe.tp_mfma_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.POINTER(C.c_double), C.c_void_p]
         scratch = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
         best = 0.0
         for _ in range(3):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
-            flops = T.tp_mfma_probe(scratch, 40000)
+            fl = C.c_double()
+            st = probe.tp_mfma_probe(scratch.data_ptr(), scratch.numel() * 4, 40000, C.byref(fl), stream.cuda_stream)
+            assert st == 0, f"tp_mfma_probe failed with status {st}"
+            flops = fl.value
             e1.record(stream)
             torch.cuda.synchronize()
             best = max(best, flops / e0.elapsed_time(e1) / 1e9)

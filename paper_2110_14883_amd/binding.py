@@ -3,6 +3,8 @@ marshalling only.  Tensors are torch CUDA(ROCm) tensors used purely as device bu
 data_ptr(), row stride and dtype are handed to the library; nothing is computed here."""
 from __future__ import annotations
 
+import contextlib
+import contextvars
 import ctypes as C
 import os
 from dataclasses import dataclass
@@ -40,6 +42,31 @@ class _OBlk(C.Structure):
     _fields_ = [("ptr", C.c_void_p), ("ld", C.c_int64), ("dtype", C.c_int)]
 
 
+class _PlanOpts(C.Structure):
+    _fields_ = [("tile", C.c_int), ("split_k", C.c_int), ("group_m", C.c_int), ("rotate", C.c_int), ("trim", C.c_int)]
+
+
+# Launch-plan options handed to every *_ex call made inside `with plan_opts(...)` (tp_plan_opts_t; the
+# library itself keeps no such state).  A context variable: each thread / task has its own.
+_plan_opts: contextvars.ContextVar = contextvars.ContextVar("tp_plan_opts", default=None)
+
+
+@contextlib.contextmanager
+def plan_opts(tile: int = 0, split_k: int = 0, group_m: int = 0, rotate: int = 0, trim: int = 0):
+    """tile: 0 auto, 1 = 256x256 (four-wave kernel), 2 = 128x256, 3 = 256x128, 4 = 128x128, 5 = 256x256 on the
+    eight-wave kernel; split_k 0 auto, 1..8; group_m 0 auto, 1..64; rotate / trim: 0 auto (on), 1 on, 2 off."""
+    token = _plan_opts.set(_PlanOpts(int(tile), int(split_k), int(group_m), int(rotate), int(trim)))
+    try:
+        yield
+    finally:
+        _plan_opts.reset(token)
+
+
+def _opts():
+    o = _plan_opts.get()
+    return None if o is None else C.byref(o)
+
+
 @dataclass(frozen=True)
 class Grid:
     """1D: p = size, ri = rank.  2D: q, (ri, rj).  2.5D: q, d, (ri, rj, rk).  3D: p, (ri, rj, rk)."""
@@ -66,41 +93,52 @@ def lib() -> C.CDLL:
         L.tp_block_map.restype = C.c_int
         L.tp_block_map.argtypes = [C.POINTER(_GridS), C.POINTER(_DimsS), C.c_int, ip, i64p, i64p, i64p,
                                    ip, ip, ip, ip, ip, ip, ip]
+        po = C.POINTER(_PlanOpts)
+        ws_args = [C.POINTER(_GridS), C.POINTER(_DimsS), C.c_int]
+        fwd_args = [C.POINTER(_GridS), C.POINTER(_DimsS), C.c_int, C.POINTER(_CBlk), C.POINTER(_CBlk),
+                    C.c_void_p, C.c_int, _OBlk, _OBlk, C.c_void_p, C.c_size_t, C.c_void_p]
+        bwd_args = [C.POINTER(_GridS), C.POINTER(_DimsS), C.c_int, C.c_int,
+                    C.POINTER(_CBlk), C.POINTER(_CBlk), C.POINTER(_CBlk), C.POINTER(_CBlk),
+                    C.POINTER(_CBlk), C.POINTER(_CBlk), C.c_int, C.c_int, C.POINTER(_CBlk),
+                    _OBlk, _OBlk, _OBlk, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        part_args = [C.POINTER(_GridS), C.POINTER(_DimsS), C.c_int, C.c_int, C.POINTER(_CBlk),
+                     C.POINTER(_CBlk), C.POINTER(_OBlk), C.POINTER(_CBlk), C.POINTER(_OBlk),
+                     C.c_void_p, C.c_size_t, C.c_void_p]
         L.tp_linear_workspace_size.restype = C.c_size_t
-        L.tp_linear_workspace_size.argtypes = [C.POINTER(_GridS), C.POINTER(_DimsS), C.c_int]
+        L.tp_linear_workspace_size.argtypes = ws_args
+        L.tp_linear_workspace_size_ex.restype = C.c_size_t
+        L.tp_linear_workspace_size_ex.argtypes = ws_args + [po]
         L.tp_linear_fwd.restype = C.c_int
-        L.tp_linear_fwd.argtypes = [C.POINTER(_GridS), C.POINTER(_DimsS), C.c_int, C.POINTER(_CBlk), C.POINTER(_CBlk),
-                                    C.c_void_p, C.c_int, _OBlk, _OBlk, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.tp_linear_fwd.argtypes = fwd_args
+        L.tp_linear_fwd_ex.restype = C.c_int
+        L.tp_linear_fwd_ex.argtypes = fwd_args + [po]
         L.tp_linear_bwd.restype = C.c_int
-        L.tp_linear_bwd.argtypes = [C.POINTER(_GridS), C.POINTER(_DimsS), C.c_int, C.c_int,
-                                    C.POINTER(_CBlk), C.POINTER(_CBlk), C.POINTER(_CBlk), C.POINTER(_CBlk),
-                                    C.POINTER(_CBlk), C.POINTER(_CBlk), C.c_int, C.c_int, C.POINTER(_CBlk),
-                                    _OBlk, _OBlk, _OBlk, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.tp_linear_bwd.argtypes = bwd_args
+        L.tp_linear_bwd_ex.restype = C.c_int
+        L.tp_linear_bwd_ex.argtypes = bwd_args + [po]
         L.tp_partials_map.restype = C.c_int
         L.tp_partials_map.argtypes = [C.POINTER(_GridS), C.POINTER(_DimsS), C.c_int, ip, i64p, i64p, i64p,
                                       ip, ip, ip, ip, ip, ip]
         L.tp_linear_bwd_partials.restype = C.c_int
-        L.tp_linear_bwd_partials.argtypes = [C.POINTER(_GridS), C.POINTER(_DimsS), C.c_int, C.c_int, C.POINTER(_CBlk),
-                                             C.POINTER(_CBlk), C.POINTER(_OBlk), C.POINTER(_CBlk), C.POINTER(_OBlk),
-                                             C.c_void_p, C.c_size_t, C.c_void_p]
+        L.tp_linear_bwd_partials.argtypes = part_args
+        L.tp_linear_bwd_partials_ex.restype = C.c_int
+        L.tp_linear_bwd_partials_ex.argtypes = part_args + [po]
         L.tp_bias_act.restype = C.c_int
         L.tp_bias_act.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int, _OBlk, _OBlk, C.c_int64, C.c_int64, C.c_void_p]
         L.tp_dgelu.restype = C.c_int
         L.tp_dgelu.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                C.c_int64, C.c_int64, C.c_void_p]
-        L.tp_mfma_probe.restype = C.c_int
-        L.tp_mfma_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.POINTER(C.c_double), C.c_void_p]
-        L.tp_plan_override.restype = C.c_int
-        L.tp_plan_override.argtypes = [C.c_int, C.c_int]
+        L.tp_bias_grad.restype = C.c_int
+        L.tp_bias_grad.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]
         L.tp_strerror.restype = C.c_char_p
         L.tp_strerror.argtypes = [C.c_int]
         _lib = L
     return _lib
 
 
-EXPORTS = ("tp_block_map", "tp_linear_workspace_size", "tp_linear_fwd", "tp_linear_bwd", "tp_dgelu",
-           "tp_partials_map", "tp_linear_bwd_partials", "tp_bias_act",
-           "tp_mfma_probe", "tp_plan_override", "tp_strerror")
+EXPORTS = ("tp_block_map", "tp_linear_workspace_size", "tp_linear_workspace_size_ex", "tp_linear_fwd", "tp_linear_fwd_ex",
+           "tp_linear_bwd", "tp_linear_bwd_ex", "tp_dgelu", "tp_partials_map", "tp_linear_bwd_partials",
+           "tp_linear_bwd_partials_ex", "tp_bias_act", "tp_bias_grad", "tp_strerror")
 
 
 # ----------------------------------------------------------------------------- marshalling helpers
@@ -215,16 +253,16 @@ def tp_block_map(grid: Grid, dims, pass_: int) -> dict:
 
 def tp_linear_workspace_size(grid: Grid, dims, pass_: int) -> int:
     g, d = grid._c(), _dims(dims)
-    return int(lib().tp_linear_workspace_size(C.byref(g), C.byref(d), int(pass_)))
+    return int(lib().tp_linear_workspace_size_ex(C.byref(g), C.byref(d), int(pass_), _opts()))
 
 
 def tp_linear_fwd(grid: Grid, dims, n_steps: int, x_blocks, w_blocks, bias, epi: int, y, preact=None,
                   workspace=None, stream=None) -> None:
     g, d = grid._c(), _dims(dims)
     ws, wsb = _ws(workspace)
-    st = lib().tp_linear_fwd(C.byref(g), C.byref(d), int(n_steps), _cblk_array(x_blocks, n_steps),
-                             _cblk_array(w_blocks, n_steps), _ptr(bias), int(epi), _oblk(y), _oblk(preact),
-                             ws, wsb, _stream(stream))
+    st = lib().tp_linear_fwd_ex(C.byref(g), C.byref(d), int(n_steps), _cblk_array(x_blocks, n_steps),
+                                _cblk_array(w_blocks, n_steps), _ptr(bias), int(epi), _oblk(y), _oblk(preact),
+                                ws, wsb, _stream(stream), _opts())
     _check(st, "tp_linear_fwd")
 
 
@@ -234,12 +272,12 @@ def tp_linear_bwd(grid: Grid, dims, n_steps_dx: int = 0, n_steps_dw: int = 0, dy
                   dx=None, dw=None, da_own_out=None, db=None, workspace=None, stream=None) -> None:
     g, d = grid._c(), _dims(dims)
     ws, wsb = _ws(workspace)
-    st = lib().tp_linear_bwd(C.byref(g), C.byref(d), int(n_steps_dx), int(n_steps_dw),
+    st = lib().tp_linear_bwd_ex(C.byref(g), C.byref(d), int(n_steps_dx), int(n_steps_dw),
                              _cblk_ptr(dy_own), _cblk_ptr(preact_own),
                              _cblk_array(da_row_blocks, n_steps_dx), _cblk_array(w_blocks_dx, n_steps_dx),
                              _cblk_array(x_blocks_dw, n_steps_dw), _cblk_array(da_col_blocks, n_steps_dw),
                              int(own_slot_dx), int(own_slot_dw), _cblk_ptr(dgelu_preact),
-                             _oblk(dx), _oblk(dw), _oblk(da_own_out), _ptr(db), ws, wsb, _stream(stream))
+                             _oblk(dx), _oblk(dw), _oblk(da_own_out), _ptr(db), ws, wsb, _stream(stream), _opts())
     _check(st, "tp_linear_bwd")
 
 
@@ -272,10 +310,10 @@ def tp_linear_bwd_partials(grid: Grid, dims, da_own, w_blocks_dx=None, dx_partia
     n_dw = 0 if x_blocks_dw is None else len(x_blocks_dw)
     if (dx_partials is not None and len(dx_partials) != n_dx) or (dw_partials is not None and len(dw_partials) != n_dw):
         raise ValueError("one output block per operand block")
-    st = lib().tp_linear_bwd_partials(C.byref(g), C.byref(d), n_dx, n_dw, _cblk_ptr(da_own),
+    st = lib().tp_linear_bwd_partials_ex(C.byref(g), C.byref(d), n_dx, n_dw, _cblk_ptr(da_own),
                                       _cblk_array(w_blocks_dx, n_dx), _oblk_array(dx_partials, n_dx),
                                       _cblk_array(x_blocks_dw, n_dw), _oblk_array(dw_partials, n_dw),
-                                      ws, wsb, _stream(stream))
+                                      ws, wsb, _stream(stream), _opts())
     _check(st, "tp_linear_bwd_partials")
 
 
@@ -287,13 +325,8 @@ def tp_bias_act(c, bias, epi: int, y, preact=None, rows: int | None = None, cols
     _check(st, "tp_bias_act")
 
 
-def tp_mfma_probe(scratch, iters: int, stream=None) -> float:
-    """Enqueues the MFMA-only loop; returns the number of flops the launch performs."""
-    flops = C.c_double()
-    ws, wsb = _ws(scratch)
-    _check(lib().tp_mfma_probe(ws, wsb, int(iters), C.byref(flops), _stream(stream)), "tp_mfma_probe")
-    return flops.value
-
-
-def tp_plan_override(key: int, value: int) -> None:
-    _check(lib().tp_plan_override(int(key), int(value)), "tp_plan_override")
+def tp_bias_grad(da, db, rows: int | None = None, cols: int | None = None, stream=None) -> None:
+    if rows is None:
+        rows, cols = int(da.shape[0]), int(da.shape[1])
+    a = _cblk(da)
+    _check(lib().tp_bias_grad(a.ptr, a.ld, int(rows), int(cols), _ptr(db), _stream(stream)), "tp_bias_grad")

@@ -14,8 +14,10 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 OBJ_DIR = os.path.join(CSRC, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libtplinear.so")
+PROBE_LIB_PATH = os.path.join(PKG_DIR, "libtpprobe.so")      # bench-only measurement aid (tp_probe.hip)
 SOURCES = ["tp_kernels.hip", "tp_gemm4.hip", "tp_api.cpp"]
-HEADERS = [os.path.join(ROOT, "include", "tp_linear.h"), os.path.join(CSRC, "tp_internal.h"), os.path.join(CSRC, "tp_device.h")]
+PROBE_SOURCE = "tp_probe.hip"
+HEADERS = [os.path.join(ROOT, "include", "tp_linear.h"), os.path.join(ROOT, "include", "tp_probe.h"), os.path.join(CSRC, "tp_internal.h"), os.path.join(CSRC, "tp_device.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
@@ -44,7 +46,7 @@ def build_library(verbose: bool = True, extra_flags: list[str] | None = None, fo
     os.makedirs(OBJ_DIR, exist_ok=True)
     newest_hdr = max(os.path.getmtime(h) for h in HEADERS)
     jobs, objs = [], []
-    for src in SOURCES:
+    for src in SOURCES + [PROBE_SOURCE]:
         path = os.path.join(CSRC, src)
         obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
         objs.append(obj)
@@ -55,7 +57,8 @@ def build_library(verbose: bool = True, extra_flags: list[str] | None = None, fo
                          "-c", path, "-o", obj])
     with ThreadPoolExecutor(max_workers=4) as ex:
         list(ex.map(lambda c: _run(c, verbose), jobs))
-    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH], verbose)
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs[:-1], "-o", LIB_PATH], verbose)
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", objs[-1], "-o", PROBE_LIB_PATH], verbose)
     return LIB_PATH
 
 

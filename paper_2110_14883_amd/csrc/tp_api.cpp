@@ -12,10 +12,37 @@ using namespace tpl;
 
 namespace {
 
-constexpr int kCUs = 256;                       // MI355X compute units
+constexpr int kCUs = 256;                       // MI355X compute units (8 XCDs x 32): the tile order and the plan assume it
 constexpr int64_t kMaxLd = (int64_t)1 << 21;    // keeps every in-tile byte offset below 2^31
 
-std::atomic<int> g_tile_override{0}, g_split_override{0}, g_group_override{0}, g_rotate{1}, g_trim{1}, g_w4{1};
+// Launch-plan options of one call, resolved from the caller's tp_plan_opts_t (NULL = automatic).
+struct Opts { int tile, split, group, rotate, trim; bool eight_wave; };
+int resolve_opts(const tp_plan_opts_t* o, Opts* r) {
+    *r = Opts{0, 0, 0, 1, 1, false};
+    if (!o) return TP_OK;
+    if (o->tile < 0 || o->tile > 5 || o->split_k < 0 || o->split_k > 8 || o->group_m < 0 || o->group_m > 64 ||
+        o->rotate < 0 || o->rotate > 2 || o->trim < 0 || o->trim > 2)
+        return TP_ERR_MODE;
+    r->tile = o->tile == 5 ? (int)TILE_256x256 : o->tile;
+    r->eight_wave = o->tile == 5;
+    r->split = o->split_k; r->group = o->group_m;
+    r->rotate = o->rotate != 2; r->trim = o->trim != 2;
+    return TP_OK;
+}
+
+// The device must be the one the kernels are laid out for: checked once per device.
+int check_device() {
+    static std::atomic<uint64_t> ok_mask{0}, bad_mask{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return TP_ERR_HIP;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (ok_mask.load(std::memory_order_relaxed) & bit) return TP_OK;
+    if (bad_mask.load(std::memory_order_relaxed) & bit) return TP_ERR_HIP;
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return TP_ERR_HIP;
+    (cus == kCUs ? ok_mask : bad_mask).fetch_or(bit, std::memory_order_relaxed);
+    return cus == kCUs ? TP_OK : TP_ERR_HIP;
+}
 
 struct Chunks { int rc, kc, cc; };              // row chunks of X/Y, col chunks of X (= row chunks of W), col chunks of W/Y
 
@@ -140,14 +167,12 @@ struct Plan {
 // Cost model: (waves of workgroups) x (K tiles per workgroup) x (tile area), plus the fp32
 // round trip of the partials when K is split.
 // groups > 1: that many products of the same extents share one launch (tiles_m, tiles_n stay per product).
-Plan plan_whole(int64_t m, int64_t n, int64_t k, int n_steps, int groups, double* cost_out) {
+Plan plan_whole(const Opts& o, int64_t m, int64_t n, int64_t k, int n_steps, int groups, double* cost_out) {
     const int64_t T = (int64_t)n_steps * ((k + 63) / 64);
     Plan best{};
     double best_cost = 1e300;
     const int tile_ids[4] = {TILE_256x256, TILE_128x256, TILE_256x128, TILE_128x128};
-    const int forced_split = g_split_override.load();
-    int forced_tile = g_tile_override.load();
-    if (forced_tile == TILE_256x256_W4) forced_tile = TILE_256x256;
+    const int forced_split = o.split, forced_tile = o.tile;
     for (int ti = 0; ti < 4; ++ti) {
         if (forced_tile && tile_ids[ti] != forced_tile) continue;
         int bm, bn;
@@ -177,8 +202,7 @@ Plan plan_whole(int64_t m, int64_t n, int64_t k, int n_steps, int groups, double
     if (best.tile_id == 0) {           // overrides left nothing admissible: fall back to the safe default
         best = Plan{TILE_256x256, 256, 256, (int)((m + 255) / 256), (int)((n + 255) / 256), 1, 4, groups, 0, 0, 0, 0, 0};
     }
-    const int go = g_group_override.load();
-    best.group_m = go > 0 ? go : 4;
+    best.group_m = o.group > 0 ? o.group : 4;
     if (cost_out) *cost_out = best_cost;
     return best;
 }
@@ -189,14 +213,13 @@ double tile_cost(int bm, int bn, int64_t T) {
     return (double)T * ((double)bm * bn * 64 * 2 / 4096.0 / 0.6 * penalty) + 20000.0;
 }
 
-Plan make_plan(int64_t m, int64_t n, int64_t k, int n_steps, int groups = 1) {
+Plan make_plan(const Opts& o, int64_t m, int64_t n, int64_t k, int n_steps, int groups = 1) {
     double whole_cost = 0.0;
-    Plan best = plan_whole(m, n, k, n_steps, groups, &whole_cost);
-    if (groups != 1 || !g_trim.load() || g_split_override.load() > 1) return best;
+    Plan best = plan_whole(o, m, n, k, n_steps, groups, &whole_cost);
+    if (groups != 1 || !o.trim || o.split > 1) return best;
     const int64_t T = (int64_t)n_steps * ((k + 63) / 64);
     const int tile_ids[4] = {TILE_256x256, TILE_128x256, TILE_256x128, TILE_128x128};
-    int forced_tile = g_tile_override.load();
-    if (forced_tile == TILE_256x256_W4) forced_tile = TILE_256x256;
+    const int forced_tile = o.tile;
     double best_cost = whole_cost;
     for (int ti = 0; ti < 4; ++ti) {
         if (forced_tile && tile_ids[ti] != forced_tile) continue;
@@ -209,7 +232,7 @@ Plan make_plan(int64_t m, int64_t n, int64_t k, int n_steps, int groups = 1) {
         if (tail_rows_tiles >= tm) continue;
         const int64_t m_main = (tm - tail_rows_tiles) * bm;
         double tail_cost = 0.0;
-        const Plan tail = plan_whole(m - m_main, n, k, n_steps, 1, &tail_cost);
+        const Plan tail = plan_whole(o, m - m_main, n, k, n_steps, 1, &tail_cost);
         const double cost = (double)((tiles - rem) / kCUs) * tile_cost(bm, bn, T) + tail_cost + 15000.0;   // + one more launch
         if (cost < best_cost) {
             best_cost = cost;
@@ -247,37 +270,22 @@ struct Product {                 // one validated GEMM ready to launch
     int form; Plan plan; GemmArgs args; bool active;
 };
 
-int run_one(int form, int tile_id, int split_k, const GemmArgs& a, hipStream_t stream);
-
-int run_product(const Product& pr, void* workspace, hipStream_t stream) {
-    GemmArgs a = pr.args;
-    a.ws = static_cast<float*>(workspace);
-    const Plan& pl = pr.plan;
-    if (pl.m_main <= 0) return run_one(pr.form, pl.tile_id, pl.split_k, a, stream);
-    // main launch: rows [0, m_main), a whole number of rounds
-    const int64_t m = a.M, m0 = pl.m_main;
-    GemmArgs mainp = a;
-    mainp.M = (int32_t)m0;
-    if (int e = run_one(pr.form, pl.tile_id, 1, mainp, stream)) return e;
-    // tail launch: rows [m_main, m) through shifted pointers, with its own tile shape and K split
-    GemmArgs tail = a;
-    tail.M = (int32_t)(m - m0);
-    tail.tiles_m = pl.tail_tiles_m; tail.tiles_n = pl.tail_tiles_n; tail.split_k = pl.tail_split;
-    for (int k = 0; k < a.n_steps; ++k) {
-        const char* ap = static_cast<const char*>(a.a[k]);
-        tail.a[k] = pr.form == FORM_TN ? ap + m0 * 2 : ap + m0 * (int64_t)a.lda[k] * 2;    // TN: A is [k][m], else [m][k]
+// The four-wave stream kernel keeps one buffer descriptor per (C tile, step) and moves 32-bit lane
+// offsets along K: every offset it can form must stay below 2^31.
+bool w4_eligible(int form, const GemmArgs& a) {
+    const bool a_kc = form != FORM_TN, b_kc = form == FORM_NT;
+    const int slots = a.n_groups > 1 ? a.n_groups : a.n_steps;
+    for (int s = 0; s < slots; ++s) {
+        const int64_t lda = a.lda[s], ldb = a.ldb[s], K = a.K;
+        if (a_kc ? (255 * lda + K) * 2 >= ((int64_t)1 << 31) : (K * lda + 256) * 2 >= ((int64_t)1 << 31)) return false;
+        if (b_kc ? (255 * ldb + K) * 2 >= ((int64_t)1 << 31) : (K * ldb + 256) * 2 >= ((int64_t)1 << 31)) return false;
     }
-    tail.out = static_cast<char*>(a.out) + m0 * a.ldo * (a.out_f32 ? 4 : 2);
-    if (a.pre) tail.pre = static_cast<char*>(a.pre) + m0 * a.ldp * 2;
-    if (a.dg) tail.dg = static_cast<const char*>(a.dg) + m0 * a.lddg * 2;
-    return run_one(pr.form, pl.tail_tile_id, pl.tail_split, tail, stream);
+    return true;
 }
 
-int run_one(int form, int tile_id, int split_k, const GemmArgs& a, hipStream_t stream) {
-    // 256 x 256 tiles run on the four-wave stream kernel unless the eight-wave one is asked for by id
-    if (tile_id == TILE_256x256 && (g_w4.load() || g_tile_override.load() == TILE_256x256_W4) &&
-        g_tile_override.load() != TILE_256x256)
-        tile_id = TILE_256x256_W4;
+int run_one(const Opts& o, int form, int tile_id, int split_k, const GemmArgs& a, hipStream_t stream) {
+    // 256 x 256 tiles run on the four-wave stream kernel unless the eight-wave one is asked for
+    if (tile_id == TILE_256x256 && !o.eight_wave && w4_eligible(form, a)) tile_id = TILE_256x256_W4;
     if (launch_gemm(form, tile_id, a, stream) != hipSuccess) return TP_ERR_HIP;
     if (split_k > 1) {
         const int groups = a.n_groups > 1 ? a.n_groups : 1;
@@ -292,13 +300,49 @@ int run_one(int form, int tile_id, int split_k, const GemmArgs& a, hipStream_t s
     return TP_OK;
 }
 
-void fill_common(GemmArgs& a, const Plan& p, int64_t m, int64_t n, int64_t k, int n_steps) {
+int run_product(const Opts& o, const Product& pr, void* workspace, hipStream_t stream) {
+    GemmArgs a = pr.args;
+    a.ws = static_cast<float*>(workspace);
+    const Plan& pl = pr.plan;
+    if (pl.m_main <= 0) return run_one(o, pr.form, pl.tile_id, pl.split_k, a, stream);
+    // main launch: rows [0, m_main), a whole number of rounds
+    const int64_t m = a.M, m0 = pl.m_main;
+    GemmArgs mainp = a;
+    mainp.M = (int32_t)m0;
+    if (int e = run_one(o, pr.form, pl.tile_id, 1, mainp, stream)) return e;
+    // tail launch: rows [m_main, m) through shifted pointers, with its own tile shape and K split
+    GemmArgs tail = a;
+    tail.M = (int32_t)(m - m0);
+    tail.tiles_m = pl.tail_tiles_m; tail.tiles_n = pl.tail_tiles_n; tail.split_k = pl.tail_split;
+    for (int k = 0; k < a.n_steps; ++k) {
+        const char* ap = static_cast<const char*>(a.a[k]);
+        tail.a[k] = pr.form == FORM_TN ? ap + m0 * 2 : ap + m0 * (int64_t)a.lda[k] * 2;    // TN: A is [k][m], else [m][k]
+    }
+    tail.out = static_cast<char*>(a.out) + m0 * a.ldo * (a.out_f32 ? 4 : 2);
+    if (a.pre) tail.pre = static_cast<char*>(a.pre) + m0 * a.ldp * 2;
+    if (a.dg) tail.dg = static_cast<const char*>(a.dg) + m0 * a.lddg * 2;
+    return run_one(o, pr.form, pl.tail_tile_id, pl.tail_split, tail, stream);
+}
+
+void fill_common(const Opts& o, GemmArgs& a, const Plan& p, int64_t m, int64_t n, int64_t k, int n_steps) {
     std::memset(&a, 0, sizeof(a));
     a.M = (int32_t)m; a.N = (int32_t)n; a.K = (int32_t)k; a.n_steps = n_steps;
     a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.split_k = p.split_k; a.group_m = p.group_m;
     a.max_workgroups = kCUs;
-    a.rotate = g_rotate.load();
+    a.rotate = o.rotate;
 }
+
+bool ws_ok(size_t need, const void* workspace, size_t bytes) {
+    return need == 0 || (workspace && bytes >= need && aligned16(workspace));
+}
+
+// byte range of an fp32 output block [rows, cols] with leading dimension ld
+struct Range { uintptr_t lo, hi; };
+Range out_range(const tp_oblk_t& b, int64_t rows, int64_t cols) {
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(b.ptr);
+    return Range{lo, lo + (uintptr_t)(((rows - 1) * b.ld + cols) * 4)};
+}
+bool overlap(const Range& a, const Range& b) { return a.lo < b.hi && b.lo < a.hi; }
 
 }  // namespace
 
@@ -325,34 +369,34 @@ int tp_block_map(const tp_grid_t* grid, const tp_dims_t* dims, int pass, int* n_
     return TP_OK;
 }
 
-size_t tp_linear_workspace_size(const tp_grid_t* grid, const tp_dims_t* dims, int pass) {
+size_t tp_linear_workspace_size_ex(const tp_grid_t* grid, const tp_dims_t* dims, int pass, const tp_plan_opts_t* opts) {
+    Opts o;
+    if (resolve_opts(opts, &o) != TP_OK) return 0;
     if (pass == TP_PASS_DX_PARTIALS || pass == TP_PASS_DW_PARTIALS) {
         PartialsShare ps;
         if (build_partials(grid, dims, pass, &ps) != TP_OK) return 0;
-        size_t worst = 0;
+        size_t worst = 0;               // any number of products 1 .. n_steps may be asked for
         for (int groups = 1; groups <= ps.n_steps; ++groups)
-            worst = std::max(worst, ws_bytes_for(make_plan(ps.m, ps.n, ps.k, 1, groups), ps.m, ps.n));
-        if (g_split_override.load() > 1)
-            worst = std::max(worst, (size_t)g_split_override.load() * ps.n_steps * ps.m * ps.n * sizeof(float));
+            worst = std::max(worst, ws_bytes_for(make_plan(o, ps.m, ps.n, ps.k, 1, groups), ps.m, ps.n));
         return worst;
     }
     Share s;
     if (build_share(grid, dims, pass, &s) != TP_OK) return 0;
-    // independent of overrides and of n_steps: the bound every plan respects (split <= 8 only when
-    // tiles are few; a plan never needs more than 4 planes unless m*n is small) -- report the worst
-    // plane count any admissible plan can pick for this shape
-    size_t worst = 0;
-    for (int steps = 1; steps <= s.n_steps; ++steps) {
-        Plan p = make_plan(s.m, s.n, s.k, steps);
-        worst = std::max(worst, ws_bytes_for(p, s.m, s.n));
-    }
-    if (g_split_override.load() > 1) worst = std::max(worst, (size_t)g_split_override.load() * s.m * s.n * sizeof(float));
+    size_t worst = 0;                   // any prefix 1 .. n_steps of the steps may be asked for
+    for (int steps = 1; steps <= s.n_steps; ++steps)
+        worst = std::max(worst, ws_bytes_for(make_plan(o, s.m, s.n, s.k, steps), s.m, s.n));
     return worst;
 }
 
-int tp_linear_fwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps, const tp_cblk_t* x_blocks,
-                  const tp_cblk_t* w_blocks, const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact,
-                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+size_t tp_linear_workspace_size(const tp_grid_t* grid, const tp_dims_t* dims, int pass) {
+    return tp_linear_workspace_size_ex(grid, dims, pass, nullptr);
+}
+
+int tp_linear_fwd_ex(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps, const tp_cblk_t* x_blocks,
+                     const tp_cblk_t* w_blocks, const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact,
+                     void* workspace, size_t workspace_bytes, void* hip_stream, const tp_plan_opts_t* opts) {
+    Opts o;
+    if (int e = resolve_opts(opts, &o)) return e;
     Share s;
     if (int e = build_share(grid, dims, TP_PASS_FWD, &s)) return e;
     if (!x_blocks || !w_blocks) return TP_ERR_NULL;
@@ -360,7 +404,7 @@ int tp_linear_fwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps, con
     if (epi != TP_EPI_NONE && epi != TP_EPI_BIAS && epi != TP_EPI_BIAS_GELU) return TP_ERR_MODE;
     if (epi != TP_EPI_NONE && !bias) return TP_ERR_NULL;
     if (bias && !aligned16(bias)) return TP_ERR_ALIGN;
-    if (grid->mode == TP_MODE_3D_GATHERED) {      // a partial over a cube axis: bias and GeLU come after the summation
+    if (s.partial) {                    // an additive partial: bias and GeLU come after the summation
         if (epi != TP_EPI_NONE || preact.ptr) return TP_ERR_MODE;
         if (y.ptr && y.dtype != TP_F32) return TP_ERR_DTYPE;
     }
@@ -374,13 +418,13 @@ int tp_linear_fwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps, con
         if (int e = check_oblk(preact, s.n, false)) return e;
         if (preact.dtype != TP_BF16) return TP_ERR_DTYPE;
     }
-    Plan p = make_plan(s.m, s.n, s.k, n_steps);
-    const size_t need = ws_bytes_for(p, s.m, s.n);
-    if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return TP_ERR_WORKSPACE;
+    Plan p = make_plan(o, s.m, s.n, s.k, n_steps);
+    if (!ws_ok(ws_bytes_for(p, s.m, s.n), workspace, workspace_bytes)) return TP_ERR_WORKSPACE;
+    if (int e = check_device()) return e;
 
     Product pr{};
     pr.form = FORM_NN; pr.plan = p;
-    fill_common(pr.args, p, s.m, s.n, s.k, n_steps);
+    fill_common(o, pr.args, p, s.m, s.n, s.k, n_steps);
     for (int k = 0; k < n_steps; ++k) {
         pr.args.a[k] = x_blocks[k].ptr; pr.args.lda[k] = (int32_t)x_blocks[k].ld;
         pr.args.b[k] = w_blocks[k].ptr; pr.args.ldb[k] = (int32_t)w_blocks[k].ld;
@@ -389,14 +433,24 @@ int tp_linear_fwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps, con
     pr.args.pre = preact.ptr; pr.args.ldp = preact.ld;
     pr.args.bias = epi == TP_EPI_NONE ? nullptr : bias;
     pr.args.gelu = epi == TP_EPI_BIAS_GELU;
-    return run_product(pr, workspace, static_cast<hipStream_t>(hip_stream));
+    return run_product(o, pr, workspace, static_cast<hipStream_t>(hip_stream));
 }
 
-int tp_linear_bwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_dx, int n_steps_dw,
-                  const tp_cblk_t* dy_own, const tp_cblk_t* preact_own, const tp_cblk_t* da_row_blocks,
-                  const tp_cblk_t* w_blocks_dx, const tp_cblk_t* x_blocks_dw, const tp_cblk_t* da_col_blocks,
-                  int own_slot_dx, int own_slot_dw, const tp_cblk_t* dgelu_preact, tp_oblk_t dx, tp_oblk_t dw,
-                  tp_oblk_t da_own_out, void* db_f32, void* workspace, size_t workspace_bytes, void* hip_stream) {
+int tp_linear_fwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps, const tp_cblk_t* x_blocks,
+                  const tp_cblk_t* w_blocks, const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact,
+                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return tp_linear_fwd_ex(grid, dims, n_steps, x_blocks, w_blocks, bias, epi, y, preact, workspace, workspace_bytes,
+                            hip_stream, nullptr);
+}
+
+int tp_linear_bwd_ex(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_dx, int n_steps_dw,
+                     const tp_cblk_t* dy_own, const tp_cblk_t* preact_own, const tp_cblk_t* da_row_blocks,
+                     const tp_cblk_t* w_blocks_dx, const tp_cblk_t* x_blocks_dw, const tp_cblk_t* da_col_blocks,
+                     int own_slot_dx, int own_slot_dw, const tp_cblk_t* dgelu_preact, tp_oblk_t dx, tp_oblk_t dw,
+                     tp_oblk_t da_own_out, void* db_f32, void* workspace, size_t workspace_bytes, void* hip_stream,
+                     const tp_plan_opts_t* opts) {
+    Opts o;
+    if (int e = resolve_opts(opts, &o)) return e;
     Share sf, sx, sw;
     if (int e = build_share(grid, dims, TP_PASS_FWD, &sf)) return e;
     if (int e = build_share(grid, dims, TP_PASS_DX, &sx)) return e;
@@ -425,8 +479,12 @@ int tp_linear_bwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_dx, 
         if (!da_row_blocks || !w_blocks_dx) return TP_ERR_NULL;
         if (n_steps_dx < 1 || n_steps_dx > sx.n_steps) return TP_ERR_SHAPE;
         if (own_slot_dx >= n_steps_dx) return TP_ERR_SHAPE;
-        Plan p = make_plan(sx.m, sx.n, sx.k, n_steps_dx);
-        fill_common(px.args, p, sx.m, sx.n, sx.k, n_steps_dx);
+        if (sx.partial) {               // a summand of a reduction: fp32, and GeLU' belongs after the sum
+            if (dgelu_preact) return TP_ERR_MODE;
+            if (dx.dtype != TP_F32) return TP_ERR_DTYPE;
+        }
+        Plan p = make_plan(o, sx.m, sx.n, sx.k, n_steps_dx);
+        fill_common(o, px.args, p, sx.m, sx.n, sx.k, n_steps_dx);
         for (int k = 0; k < n_steps_dx; ++k) {
             const tp_cblk_t& a = (k == own_slot_dx) ? own_blk : da_row_blocks[k];
             if (int e = check_cblk(a, sx.k)) return e;
@@ -448,8 +506,8 @@ int tp_linear_bwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_dx, 
         if (!x_blocks_dw || !da_col_blocks) return TP_ERR_NULL;
         if (n_steps_dw < 1 || n_steps_dw > sw.n_steps) return TP_ERR_SHAPE;
         if (own_slot_dw >= n_steps_dw) return TP_ERR_SHAPE;
-        Plan p = make_plan(sw.m, sw.n, sw.k, n_steps_dw);
-        fill_common(pw.args, p, sw.m, sw.n, sw.k, n_steps_dw);
+        Plan p = make_plan(o, sw.m, sw.n, sw.k, n_steps_dw);
+        fill_common(o, pw.args, p, sw.m, sw.n, sw.k, n_steps_dw);
         for (int k = 0; k < n_steps_dw; ++k) {
             const tp_cblk_t& b = (k == own_slot_dw) ? own_blk : da_col_blocks[k];
             if (int e = check_cblk(x_blocks_dw[k], sw.m)) return e;       // X block is [k = tokens][m = H_blk]
@@ -464,7 +522,9 @@ int tp_linear_bwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_dx, 
     size_t need = 0;
     if (px.active) need = std::max(need, ws_bytes_for(px.plan, sx.m, sx.n));
     if (pw.active) need = std::max(need, ws_bytes_for(pw.plan, sw.m, sw.n));
-    if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return TP_ERR_WORKSPACE;
+    if (!ws_ok(need, workspace, workspace_bytes)) return TP_ERR_WORKSPACE;
+    if (want_da || px.active || pw.active)
+        if (int e = check_device()) return e;
 
     // ---- launches (stream order: dA, db, dX, dW)
     if (want_da) {
@@ -473,9 +533,19 @@ int tp_linear_bwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_dx, 
         if (db_f32 && launch_colsum(da_own_out.ptr, da_own_out.ld, sf.m, sf.n, static_cast<float*>(db_f32), stream) != hipSuccess)
             return TP_ERR_HIP;
     }
-    if (px.active) if (int e = run_product(px, workspace, stream)) return e;
-    if (pw.active) if (int e = run_product(pw, workspace, stream)) return e;
+    if (px.active) if (int e = run_product(o, px, workspace, stream)) return e;
+    if (pw.active) if (int e = run_product(o, pw, workspace, stream)) return e;
     return TP_OK;
+}
+
+int tp_linear_bwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_dx, int n_steps_dw,
+                  const tp_cblk_t* dy_own, const tp_cblk_t* preact_own, const tp_cblk_t* da_row_blocks,
+                  const tp_cblk_t* w_blocks_dx, const tp_cblk_t* x_blocks_dw, const tp_cblk_t* da_col_blocks,
+                  int own_slot_dx, int own_slot_dw, const tp_cblk_t* dgelu_preact, tp_oblk_t dx, tp_oblk_t dw,
+                  tp_oblk_t da_own_out, void* db_f32, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return tp_linear_bwd_ex(grid, dims, n_steps_dx, n_steps_dw, dy_own, preact_own, da_row_blocks, w_blocks_dx,
+                            x_blocks_dw, da_col_blocks, own_slot_dx, own_slot_dw, dgelu_preact, dx, dw, da_own_out,
+                            db_f32, workspace, workspace_bytes, hip_stream, nullptr);
 }
 
 int tp_partials_map(const tp_grid_t* grid, const tp_dims_t* dims, int pass, int* n_steps, int64_t* m, int64_t* n,
@@ -497,9 +567,12 @@ int tp_partials_map(const tp_grid_t* grid, const tp_dims_t* dims, int pass, int*
     return TP_OK;
 }
 
-int tp_linear_bwd_partials(const tp_grid_t* grid, const tp_dims_t* dims, int n_dx, int n_dw, const tp_cblk_t* da_own,
-                           const tp_cblk_t* w_blocks_dx, const tp_oblk_t* dx_partials, const tp_cblk_t* x_blocks_dw,
-                           const tp_oblk_t* dw_partials, void* workspace, size_t workspace_bytes, void* hip_stream) {
+int tp_linear_bwd_partials_ex(const tp_grid_t* grid, const tp_dims_t* dims, int n_dx, int n_dw, const tp_cblk_t* da_own,
+                              const tp_cblk_t* w_blocks_dx, const tp_oblk_t* dx_partials, const tp_cblk_t* x_blocks_dw,
+                              const tp_oblk_t* dw_partials, void* workspace, size_t workspace_bytes, void* hip_stream,
+                              const tp_plan_opts_t* opts) {
+    Opts o;
+    if (int e = resolve_opts(opts, &o)) return e;
     PartialsShare sx, sw;
     if (int e = build_partials(grid, dims, TP_PASS_DX_PARTIALS, &sx)) return e;
     if (int e = build_partials(grid, dims, TP_PASS_DW_PARTIALS, &sw)) return e;
@@ -510,14 +583,17 @@ int tp_linear_bwd_partials(const tp_grid_t* grid, const tp_dims_t* dims, int n_d
     if (int e = check_cblk(*da_own, sx.k)) return e;                  // [M_blk, F_blk]
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
+    Range ranges[2 * TP_MAX_STEPS];
+    int n_ranges = 0;
     Product px{}; px.active = n_dx > 0;
     if (px.active) {
         if (!w_blocks_dx || !dx_partials) return TP_ERR_NULL;
-        Plan p = make_plan(sx.m, sx.n, sx.k, 1, n_dx);
-        fill_common(px.args, p, sx.m, sx.n, sx.k, 1);
+        Plan p = make_plan(o, sx.m, sx.n, sx.k, 1, n_dx);
+        fill_common(o, px.args, p, sx.m, sx.n, sx.k, 1);
         for (int k = 0; k < n_dx; ++k) {
             if (int e = check_cblk(w_blocks_dx[k], sx.k)) return e;    // W block [H_blk][F_blk]: n x k
             if (int e = check_oblk(dx_partials[k], sx.n, true)) return e;
+            ranges[n_ranges++] = out_range(dx_partials[k], sx.m, sx.n);
             px.args.a[k] = da_own->ptr; px.args.lda[k] = (int32_t)da_own->ld;
             px.args.b[k] = w_blocks_dx[k].ptr; px.args.ldb[k] = (int32_t)w_blocks_dx[k].ld;
             px.args.outs[k] = dx_partials[k].ptr; px.args.ldos[k] = dx_partials[k].ld;
@@ -530,11 +606,12 @@ int tp_linear_bwd_partials(const tp_grid_t* grid, const tp_dims_t* dims, int n_d
     Product pw{}; pw.active = n_dw > 0;
     if (pw.active) {
         if (!x_blocks_dw || !dw_partials) return TP_ERR_NULL;
-        Plan p = make_plan(sw.m, sw.n, sw.k, 1, n_dw);
-        fill_common(pw.args, p, sw.m, sw.n, sw.k, 1);
+        Plan p = make_plan(o, sw.m, sw.n, sw.k, 1, n_dw);
+        fill_common(o, pw.args, p, sw.m, sw.n, sw.k, 1);
         for (int k = 0; k < n_dw; ++k) {
             if (int e = check_cblk(x_blocks_dw[k], sw.m)) return e;    // X block [M_blk][H_blk]: k x m
             if (int e = check_oblk(dw_partials[k], sw.n, true)) return e;
+            ranges[n_ranges++] = out_range(dw_partials[k], sw.m, sw.n);
             pw.args.a[k] = x_blocks_dw[k].ptr; pw.args.lda[k] = (int32_t)x_blocks_dw[k].ld;
             pw.args.b[k] = da_own->ptr; pw.args.ldb[k] = (int32_t)da_own->ld;
             pw.args.outs[k] = dw_partials[k].ptr; pw.args.ldos[k] = dw_partials[k].ld;
@@ -544,13 +621,24 @@ int tp_linear_bwd_partials(const tp_grid_t* grid, const tp_dims_t* dims, int n_d
         pw.args.tiles_m = p.tiles_m * n_dw;                            // the products stacked along M
         pw.form = FORM_TN; pw.plan = p;
     }
+    for (int i = 0; i < n_ranges; ++i)
+        for (int j = i + 1; j < n_ranges; ++j)
+            if (overlap(ranges[i], ranges[j])) return TP_ERR_SHAPE;
     size_t need = 0;
     if (px.active) need = std::max(need, ws_bytes_for(px.plan, sx.m, sx.n));
     if (pw.active) need = std::max(need, ws_bytes_for(pw.plan, sw.m, sw.n));
-    if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return TP_ERR_WORKSPACE;
-    if (px.active) if (int e = run_product(px, workspace, stream)) return e;
-    if (pw.active) if (int e = run_product(pw, workspace, stream)) return e;
+    if (!ws_ok(need, workspace, workspace_bytes)) return TP_ERR_WORKSPACE;
+    if (int e = check_device()) return e;
+    if (px.active) if (int e = run_product(o, px, workspace, stream)) return e;
+    if (pw.active) if (int e = run_product(o, pw, workspace, stream)) return e;
     return TP_OK;
+}
+
+int tp_linear_bwd_partials(const tp_grid_t* grid, const tp_dims_t* dims, int n_dx, int n_dw, const tp_cblk_t* da_own,
+                           const tp_cblk_t* w_blocks_dx, const tp_oblk_t* dx_partials, const tp_cblk_t* x_blocks_dw,
+                           const tp_oblk_t* dw_partials, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return tp_linear_bwd_partials_ex(grid, dims, n_dx, n_dw, da_own, w_blocks_dx, dx_partials, x_blocks_dw, dw_partials,
+                                     workspace, workspace_bytes, hip_stream, nullptr);
 }
 
 int tp_bias_act(const void* c, int64_t ld_c, const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact, int64_t rows,
@@ -585,40 +673,28 @@ int tp_dgelu(const void* dy, int64_t ld_dy, const void* preact, int64_t ld_pre, 
     return TP_OK;
 }
 
-int tp_mfma_probe(void* scratch, size_t scratch_bytes, int iters, double* flops, void* hip_stream) {
-    if (!scratch || !flops) return TP_ERR_NULL;
-    if (iters < 1) return TP_ERR_SHAPE;
-    if (scratch_bytes < (size_t)kCUs * 256 * sizeof(float) || !aligned16(scratch)) return TP_ERR_WORKSPACE;
-    // 256 workgroups x 4 waves x iters x 8 MFMAs of 32x32x16 (32768 flops each)
-    *flops = (double)kCUs * 4.0 * (double)iters * 8.0 * 32768.0;
-    if (launch_mfma_probe(static_cast<float*>(scratch), kCUs, iters, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+int tp_bias_grad(const void* da, int64_t ld_da, int64_t rows, int64_t cols, void* db_f32, void* hip_stream) {
+    if (!da || !db_f32) return TP_ERR_NULL;
+    if (rows < 0 || cols < 0) return TP_ERR_SHAPE;
+    if (!aligned16(da) || !aligned16(db_f32) || (cols & 7) || (ld_da & 7)) return TP_ERR_ALIGN;
+    if (ld_da < cols) return TP_ERR_SHAPE;
+    if (cols == 0) return TP_OK;
+    if (launch_colsum(da, ld_da, rows, cols, static_cast<float*>(db_f32), static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return TP_ERR_HIP;
     return TP_OK;
-}
-
-int tp_plan_override(int key, int value) {
-    switch (key) {
-        case 0: if (value < 0 || value > TILE_256x256_W4) return TP_ERR_MODE; g_tile_override = value; return TP_OK;
-        case 1: if (value < 0 || value > 8) return TP_ERR_MODE; g_split_override = value; return TP_OK;
-        case 2: if (value < 0 || value > 64) return TP_ERR_MODE; g_group_override = value; return TP_OK;
-        case 3: g_rotate = value != 0; return TP_OK;
-        case 4: g_trim = value != 0; return TP_OK;
-        case 5: g_w4 = value != 0; return TP_OK;
-        default: return TP_ERR_MODE;
-    }
 }
 
 const char* tp_strerror(int status) {
     switch (status) {
         case TP_OK: return "ok";
         case TP_ERR_NULL: return "a required pointer is NULL";
-        case TP_ERR_MODE: return "unknown mode, pass, epilogue or option";
+        case TP_ERR_MODE: return "unknown mode, pass, epilogue or option, or an epilogue asked of an additive partial";
         case TP_ERR_GRID: return "grid size or rank coordinate out of range";
-        case TP_ERR_SHAPE: return "layer dimensions, leading dimension or step count do not fit the grid";
+        case TP_ERR_SHAPE: return "layer dimensions, leading dimension or step count do not fit the grid, or outputs overlap";
         case TP_ERR_ALIGN: return "pointer not 16-byte aligned, or a column extent / leading dimension not a multiple of 8";
         case TP_ERR_DTYPE: return "output dtype not supported here";
         case TP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
-        case TP_ERR_HIP: return "a HIP call failed";
+        case TP_ERR_HIP: return "a HIP call failed, or the device is not a 256-CU MI355X";
         default: return "unknown status";
     }
 }

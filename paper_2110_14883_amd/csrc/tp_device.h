@@ -3,6 +3,7 @@
 // staging classes and the tile-order map.  Included by the .hip sources only.
 #pragma once
 #include <atomic>
+#include <tuple>
 #include <type_traits>
 
 #include "tp_internal.h"
@@ -24,6 +25,17 @@ constexpr uint32_t MAX_RECORDS = 0x80000000u;
 constexpr int N_XCD = 8;
 enum { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_GELU = 2, EPI_MUL_DGELU = 3 };   // epilogue kinds compiled into the GEMM
 constexpr int EPI_BYTES_PER_WAVE = 4096;      // epilogue staging patch: 32 rows x 128 bytes per wave
+
+// Launch through the call that RETURNS the launch's own status: an error some other code left
+// behind on this thread is neither reported as ours nor cleared.
+template <class... P, class... A>
+inline hipError_t launch_kernel(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream, A... args) {
+    std::tuple<P...> vals{static_cast<P>(args)...};
+    void* ptrs[sizeof...(P)];
+    size_t i = 0;
+    std::apply([&](auto&... v) { ((ptrs[i++] = const_cast<void*>(static_cast<const void*>(&v))), ...); }, vals);
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds_bytes, stream);
+}
 
 // ---------------------------------------------------------------------------------------------
 // small device helpers

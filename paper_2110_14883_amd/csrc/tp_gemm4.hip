@@ -49,6 +49,19 @@ typedef __attribute__((address_space(3))) bf16x8_t lds_bf16x8_t;
 __device__ __forceinline__ void lds_store16(uint32_t addr, u32x4_t v) { *reinterpret_cast<lds_u32x4_t*>(addr) = v; }
 __device__ __forceinline__ bf16x8_t lds_load_frag(uint32_t addr) { return *reinterpret_cast<const lds_bf16x8_t*>(addr); }
 
+// One direct-to-LDS load: each lane's 16 bytes go from global memory straight into LDS, lane l at
+// byte lds_base + 16 l (lds_base: wave-uniform, travels in M0), without touching the vector registers.
+// Out-of-range lanes write zeros.  The compiler does not see this load: whoever reads the data waits
+// for it with wait_vm() and a barrier.
+__device__ __forceinline__ void dtl_load16(u32x4_t rsrc_words, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_base), "v"(voff), "s"(rsrc_words) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vm() {      // at most N vector-memory operations outstanding
+    static_assert(N >= 0 && N < 64);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
 constexpr int W4_THREADS = 256;
 constexpr int W4_BM = 256, W4_BN = 256;
 constexpr int W4_STAGE_STRIDE = W4_BM * BK * 2;              // 32 KB: one stage of one operand
@@ -94,6 +107,8 @@ void tp_gemm4_kernel(const GemmArgs p) {
     constexpr int TM = 4, TN = 4;                  // 32 x 32 MFMA tiles per wave along M and N
     // the transposed operand (if there is exactly one) is staged first: its reloads need the longer lead
     constexpr bool A_FIRST = A_KC ? B_KC : true;
+    // Both operands contraction-contiguous (the NT form): they go from memory to LDS directly.
+    constexpr bool DTL = A_KC && B_KC;
     static constexpr Slots SA = make_slots<A_KC, A_FIRST, B_KC>();
     static constexpr Slots SB = make_slots<B_KC, !A_FIRST, A_KC>();
 
@@ -177,6 +192,15 @@ void tp_gemm4_kernel(const GemmArgs p) {
     // the lane offsets move.  (The host sends a product here only if those offsets fit 31 bits.)
     u32x4_t sa[2][8], sb[2][8];                    // two K tiles in flight through registers
     __amdgpu_buffer_rsrc_t rs_a, rs_b;
+    // direct-to-LDS operands: descriptor words; lane offsets of loads 2 j and 2 j + 1 at k = 0 and for the
+    // fetch cursor's K tile.  Load n of wave w brings rows 32 n + 8 w .. + 7 (1 KB of LDS); lane l holds
+    // LDS position l % 8 of row 8 w + l / 8, i.e. the chunk the swizzle of lds_off() puts there, which
+    // differs between even and odd n by chunk ^ 2.
+    u32x4_t rw_a, rw_b;
+    uint32_t dl_a[2], dl_b[2], dv_a[2], dv_b[2];
+    const int d_rl = w * 8 + (l >> 3);
+    const int d_c0 = (l & 7) ^ ((d_rl >> 1) & 7) ^ (d_rl >> 4);
+    const uint32_t s_wbase = (uint32_t)(w * 1024);
     uint32_t la_off, lb_off;                       // per-lane byte offset of load 0 at k = 0 (OOB_OFFSET: lane masked)
     uint32_t va_off[2], vb_off[2];                 // the same for the K tile whose loads are being issued, and the next
     int a_step, b_step, a_kmul, b_kmul;            // bytes between a lane's loads; bytes per unit of k
@@ -192,7 +216,20 @@ void tp_gemm4_kernel(const GemmArgs p) {
         __amdgpu_buffer_rsrc_t rs;
         uint32_t lane;
         int step, kmul;
-        if constexpr (KC) {                        // [x][k]: chunk c = t % 8 of rows t / 8 + 32 i
+        if constexpr (KC && DTL) {
+            const int64_t nrec = ok ? ((int64_t)(xs - 1) * ld + p.K) * 2 : 0;
+            const uint64_t base = reinterpret_cast<uint64_t>(ptr + (int64_t)x0 * ld);
+            const u32x4_t rw = {(uint32_t)uni((int)(uint32_t)base), (uint32_t)uni((int)((uint32_t)(base >> 32) & 0xffffu)),
+                                (uint32_t)uni((int)(uint32_t)nrec), 0x00020000u};
+            if constexpr (IS_A) { rw_a = rw; a_step = uni(64 * ld); }
+            else                { rw_b = rw; b_step = uni(64 * ld); }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t off = (uint32_t)((d_rl * ld + (d_c0 ^ (2 * h)) * 8) * 2);
+                if constexpr (IS_A) dl_a[h] = off; else dl_b[h] = off;
+            }
+            return;
+        } else if constexpr (KC) {                 // [x][k]: chunk c = t % 8 of rows t / 8 + 32 i
             const int cc = t & 7, r0 = t >> 3;
             const int64_t nrec = ok ? ((int64_t)(xs - 1) * ld + p.K) * 2 : 0;
             rs = make_rsrc(uni_ptr(ptr + (int64_t)x0 * ld), nrec);
@@ -214,6 +251,15 @@ void tp_gemm4_kernel(const GemmArgs p) {
         int kt = f.kt + f.rot;
         if (kt >= KT) kt -= KT;
         const int k0 = kt * BK;
+        if constexpr (DTL) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const bool kok = (k0 + (d_c0 ^ (2 * h)) * 8) < p.K;
+                dv_a[h] = kok ? dl_a[h] + (uint32_t)(k0 * 2) : OOB_OFFSET;
+                dv_b[h] = kok ? dl_b[h] + (uint32_t)(k0 * 2) : OOB_OFFSET;
+            }
+            return;
+        }
         if constexpr (A_KC) va_off[Q] = (k0 + (t & 7) * 8) < p.K ? la_off + (uint32_t)(k0 * 2) : OOB_OFFSET;
         else                va_off[Q] = la_off + (uint32_t)(k0 * a_kmul);
         if constexpr (B_KC) vb_off[Q] = (k0 + (t & 7) * 8) < p.K ? lb_off + (uint32_t)(k0 * 2) : OOB_OFFSET;
@@ -249,6 +295,14 @@ void tp_gemm4_kernel(const GemmArgs p) {
         // (register set R is refilled while stage 1 - R is multiplied; the offsets of that K tile are copy 1 - R)
         if constexpr (IS_A) sa[R][n] = buf_load16(rs_a, va_off[1 - R] + (uint32_t)(n * a_step));
         else                sb[R][n] = buf_load16(rs_b, vb_off[1 - R] + (uint32_t)(n * b_step));
+    };
+    // n-th direct-to-LDS load of an operand into stage S
+    auto dtl1 = [&](auto is_a, auto n_, auto S_) __attribute__((always_inline)) {
+        constexpr bool IS_A = decltype(is_a)::value;
+        constexpr int n = decltype(n_)::value;
+        constexpr uint32_t dst = (IS_A ? 0u : (uint32_t)W4_B_BASE) + decltype(S_)::value * W4_STAGE_STRIDE + n * 4096;
+        if constexpr (IS_A) dtl_load16(rw_a, dv_a[n & 1] + (uint32_t)(n * a_step), s_wbase + dst);
+        else                dtl_load16(rw_b, dv_b[n & 1] + (uint32_t)(n * b_step), s_wbase + dst);
     };
     // n-th LDS write of an operand from register set R into stage S.  A transposed operand's write is
     // row x + n of its 8 x 8 block: word wd = n / 2 of the eight loaded rows, low or high halves, formed
@@ -317,6 +371,7 @@ void tp_gemm4_kernel(const GemmArgs p) {
         constexpr int S = decltype(S_)::value;
         using SR = std::integral_constant<int, S>;          // stage read
         using SW = std::integral_constant<int, 1 - S>;      // stage refilled, from register set 1 - S
+        [[maybe_unused]] SR sr_unused{};
         static_for<64>([&](auto s_) __attribute__((always_inline)) {
             constexpr int s = decltype(s_)::value;
             constexpr int ks = s >> 4, i = (s >> 2) & 3, j = s & 3;
@@ -324,6 +379,7 @@ void tp_gemm4_kernel(const GemmArgs p) {
                 // every LDS write of this K tile was issued before here; after the barrier the other
                 // stage is complete, and nobody reads the current one any more (the step-3 fragments
                 // were requested during step 2 and have arrived: the barrier waits for them)
+                if constexpr (DTL) wait_vm<0>();    // this wave's direct-to-LDS loads of the next K tile have landed
                 __syncthreads();
             }
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks & 1][j], fa[ks & 1][i], acc[i][j], 0, 0, 0);
@@ -336,7 +392,17 @@ void tp_gemm4_kernel(const GemmArgs p) {
                 else if constexpr (n <= 4) read_b(KN{}, std::integral_constant<int, n - 1>{}, ST{});
                 else                       read_a(KN{}, std::integral_constant<int, n - 4>{}, ST{});
             }
-            static_for<8>([&](auto n_) __attribute__((always_inline)) {
+            if constexpr (DTL) {
+                // The K tile at the fetch cursor: operand B during MFMA step 0 (into the stage being
+                // refilled), then the cursor moves on, and after the barrier operand A of the following
+                // K tile goes into the stage this body has just finished reading.
+                if constexpr ((s & 1) == 1 && s < 16) dtl1(std::false_type{}, std::integral_constant<int, s / 2>{}, SW{});
+                if constexpr ((s & 1) == 1 && s > 48) dtl1(std::true_type{}, std::integral_constant<int, (s - 49) / 2>{}, SR{});
+                if constexpr (s == 38) advance_fast();
+                if constexpr (s == 40) { if (f_reopen) advance_slow(); }
+                if constexpr (s == 42) prep_tile(SW{});
+            }
+            if constexpr (!DTL) static_for<8>([&](auto n_) __attribute__((always_inline)) {
                 constexpr int n = decltype(n_)::value;
                 if constexpr (!A_KC && SA.pm[n] == s) perm1(std::true_type{}, n_, SW{});
                 if constexpr (!B_KC && SB.pm[n] == s) perm1(std::false_type{}, n_, SW{});
@@ -347,13 +413,15 @@ void tp_gemm4_kernel(const GemmArgs p) {
             });
             // the fetch cursor moves on to the K tile the NEXT body loads, and that tile's lane offsets go
             // into the other copy; descriptors stay as they are until this tile's last load has been issued
-            if constexpr (s == 3) advance_fast();
-            if constexpr (s == 9) prep_tile(SW{});
+            if constexpr (!DTL && s == 3) advance_fast();
+            if constexpr (!DTL && s == 9) prep_tile(SW{});
             __builtin_amdgcn_sched_barrier(0);
         });
-        if (f_reopen) {
-            advance_slow();
-            prep_tile(SW{});
+        if constexpr (!DTL) {
+            if (f_reopen) {
+                advance_slow();
+                prep_tile(SW{});
+            }
         }
     };
 
@@ -438,7 +506,8 @@ void tp_gemm4_kernel(const GemmArgs p) {
         // The loads of the K tile after next are in flight.  Loads and stores complete out of order
         // with respect to each other, so a wait for those loads issued after the first store would
         // have to wait for every store as well: take the loads in before the first store instead.
-        __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0), nothing else
+        // (Direct-to-LDS loads feed no register: nothing to take in.)
+        if constexpr (!DTL) wait_vm<0>();
         if (partial) {
             float* const wsz = p.ws + ((int64_t)c.z * p.n_groups + c.g) * p.M * p.N;
 #pragma unroll
@@ -474,6 +543,16 @@ void tp_gemm4_kernel(const GemmArgs p) {
         static_for<8>([&](auto n_) __attribute__((always_inline)) { load1(std::integral_constant<bool, A_FIRST>{}, n_, R_); });
         static_for<8>([&](auto n_) __attribute__((always_inline)) { load1(std::integral_constant<bool, !A_FIRST>{}, n_, R_); });
     };
+    if constexpr (DTL) {
+        // K tile 0 -> stage 0 (both operands), operand A of K tile 1 -> stage 1; operand B of K tile 1 is the
+        // first thing the loop body loads
+        prep_tile(S0{});
+        static_for<8>([&](auto n_) __attribute__((always_inline)) { dtl1(std::true_type{}, n_, S0{}); });
+        static_for<8>([&](auto n_) __attribute__((always_inline)) { dtl1(std::false_type{}, n_, S0{}); });
+        move_on(S0{});
+        static_for<8>([&](auto n_) __attribute__((always_inline)) { dtl1(std::true_type{}, n_, S1{}); });
+        wait_vm<8>();
+    } else {
     prep_tile(S1{});
     load_all(S0{});                                // (set 0 takes its offsets from copy 1, set 1 from copy 0)
     move_on(S0{});
@@ -491,6 +570,7 @@ void tp_gemm4_kernel(const GemmArgs p) {
     move_on(S1{});
     load_all(S0{});
     move_on(S0{});                                 // the first loop body (stage 0) refills set 1 from copy 0
+    }
     __syncthreads();
     read_first(S0{});
 
@@ -523,8 +603,7 @@ static hipError_t launch4_one(const GemmArgs& a, hipStream_t stream) {
     }
     const int total = a.tiles_m * a.tiles_n * a.split_k;
     const unsigned grid = (unsigned)(total < a.max_workgroups ? total : a.max_workgroups);
-    hipLaunchKernelGGL((tp_gemm4_kernel<A_KC, B_KC, EPI, F32_OUT>), dim3(grid), dim3(W4_THREADS), W4_LDS_BYTES, stream, a);
-    return hipGetLastError();
+    return launch_kernel(tp_gemm4_kernel<A_KC, B_KC, EPI, F32_OUT>, dim3(grid), dim3(W4_THREADS), W4_LDS_BYTES, stream, a);
 }
 
 hipError_t launch_gemm4(int form, const GemmArgs& a, hipStream_t s) {

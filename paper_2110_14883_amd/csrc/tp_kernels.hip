@@ -414,36 +414,6 @@ __global__ __launch_bounds__(256) void tp_colsum_kernel(const uint16_t* da, int6
 }
 
 // ---------------------------------------------------------------------------------------------
-// measurement aid: register-resident MFMA-only loop (no LDS, no memory), operands with random-looking
-// bits.  What it sustains is the chip's real dense-bf16 ceiling at the clock it holds under load.
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void tp_mfma_probe_kernel(float* out, int iters, uint32_t seed) {
-    u32x4_t a0, b0;
-    uint32_t x = seed ^ (threadIdx.x * 2654435761u) ^ (blockIdx.x * 40503u);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        x = x * 1664525u + 1013904223u; a0[i] = (x & 0x807f807fu) | 0x3f003f00u;     // bf16 pairs in [0.5, 1) with random sign/mantissa
-        x = x * 1664525u + 1013904223u; b0[i] = (x & 0x807f807fu) | 0x3c003c00u;
-    }
-    const bf16x8_t a = __builtin_bit_cast(bf16x8_t, a0), b = __builtin_bit_cast(bf16x8_t, b0);
-    f32x16_t acc[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
-    }
-    float s = 0.0f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s += acc[i][v];
-    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
-}
-
-// ---------------------------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------------------------
 void tile_shape(int tile_id, int* bm, int* bn) {
@@ -473,8 +443,7 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
     // persistent: never more workgroups than the chip holds at once (one per CU with this much LDS)
     const int total = a.tiles_m * a.tiles_n * a.split_k;
     const unsigned grid = (unsigned)(total < a.max_workgroups ? total : a.max_workgroups);
-    hipLaunchKernelGGL((tp_gemm_kernel<BM, BN, A_KC, B_KC, EPI, F32_OUT>), dim3(grid), dim3(NTHREADS), lds_bytes, stream, a);
-    return hipGetLastError();
+    return launch_kernel(tp_gemm_kernel<BM, BN, A_KC, B_KC, EPI, F32_OUT>, dim3(grid), dim3(NTHREADS), lds_bytes, stream, a);
 }
 
 template <int BM, int BN>
@@ -519,18 +488,12 @@ hipError_t launch_gemm(int form, int tile_id, const GemmArgs& args, hipStream_t 
     }
 }
 
-hipError_t launch_mfma_probe(float* out, int workgroups, int iters, hipStream_t s) {
-    hipLaunchKernelGGL(tp_mfma_probe_kernel, dim3((unsigned)workgroups), dim3(256), 0, s, out, iters, 0x9E3779B9u);
-    return hipGetLastError();
-}
-
 hipError_t launch_reduce(const ReduceArgs& a, hipStream_t s) {
     const int64_t total = (int64_t)a.M * (a.N >> 2);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(tp_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
-    return hipGetLastError();
+    return launch_kernel(tp_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
 }
 
 hipError_t launch_dgelu(const void* dy, int64_t ld_dy, const void* pre, int64_t ld_pre, void* da, int64_t ld_da,
@@ -539,10 +502,9 @@ hipError_t launch_dgelu(const void* dy, int64_t ld_dy, const void* pre, int64_t 
     if (total == 0) return hipSuccess;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
-    hipLaunchKernelGGL(tp_dgelu_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const uint16_t*>(dy), ld_dy,
-                       static_cast<const uint16_t*>(pre), ld_pre, static_cast<uint16_t*>(da), ld_da, rows,
-                       (int)(cols >> 3));
-    return hipGetLastError();
+    return launch_kernel(tp_dgelu_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const uint16_t*>(dy), ld_dy,
+                         static_cast<const uint16_t*>(pre), ld_pre, static_cast<uint16_t*>(da), ld_da, rows,
+                         (int)(cols >> 3));
 }
 
 hipError_t launch_bias_act(const float* c, int64_t ldc, const void* bias, int gelu, void* y, int64_t ldy, int y_f32,
@@ -551,16 +513,14 @@ hipError_t launch_bias_act(const float* c, int64_t ldc, const void* bias, int ge
     if (total == 0) return hipSuccess;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
-    hipLaunchKernelGGL(tp_bias_act_kernel, dim3((unsigned)blocks), dim3(256), 0, s, c, ldc, static_cast<const uint16_t*>(bias),
-                       gelu, y, ldy, y_f32, static_cast<uint16_t*>(pre), ldp, rows, (int)(cols >> 2));
-    return hipGetLastError();
+    return launch_kernel(tp_bias_act_kernel, dim3((unsigned)blocks), dim3(256), 0, s, c, ldc, static_cast<const uint16_t*>(bias),
+                         gelu, y, ldy, y_f32, static_cast<uint16_t*>(pre), ldp, rows, (int)(cols >> 2));
 }
 
 hipError_t launch_colsum(const void* da, int64_t ld, int64_t rows, int64_t cols, float* out, hipStream_t s) {
     const unsigned blocks = (unsigned)((cols + 63) / 64);
-    hipLaunchKernelGGL(tp_colsum_kernel, dim3(blocks), dim3(256), 0, s, static_cast<const uint16_t*>(da), ld, rows,
-                       (int)cols, out);
-    return hipGetLastError();
+    return launch_kernel(tp_colsum_kernel, dim3(blocks), dim3(256), 0, s, static_cast<const uint16_t*>(da), ld, rows,
+                         (int)cols, out);
 }
 
 }  // namespace tpl

@@ -62,36 +62,16 @@ def check(got: np.ndarray, ref: np.ndarray, kind: str, what: str) -> None:
 
 
 def workspace_for(grid, dims) -> torch.Tensor | None:
+    """Workspace for the calls made under the plan options in force (T.plan_opts): the query and the
+    calls read the same options."""
     n = max(T.tp_linear_workspace_size(grid, dims, p) for p in (0, 1, 2))
-    # overrides may ask for more planes than the automatic plan: leave room for 8
-    mp = [T.tp_block_map(grid, dims, p) for p in (0, 1, 2)]
-    n = max(n, max(8 * x["m"] * x["n"] * 4 for x in mp) if _overrides_active else n)
     return torch.empty(max(n, 256), dtype=torch.uint8, device="cuda")
 
 
-_overrides_active = False
-
-
-class overrides:
-    """with overrides(tile=.., split=.., group=.., trim=..): plan overrides for the calls inside."""
-
-    def __init__(self, tile=0, split=0, group=0, trim=1):
-        self.v = (tile, split, group)
-        self.trim = trim
-
-    def __enter__(self):
-        global _overrides_active
-        _overrides_active = any(self.v)
-        for k, v in enumerate(self.v):
-            T.tp_plan_override(k, v)
-        T.tp_plan_override(4, self.trim)
-
-    def __exit__(self, *a):
-        global _overrides_active
-        _overrides_active = False
-        for k in range(3):
-            T.tp_plan_override(k, 0)
-        T.tp_plan_override(4, 1)
+def overrides(tile=0, split=0, group=0, trim=1, rotate=1):
+    """with overrides(tile=.., split=.., group=.., trim=.., rotate=..): plan options for the calls inside
+    (trim / rotate: 1 on, 0 off)."""
+    return T.plan_opts(tile=tile, split_k=split, group_m=group, rotate=1 if rotate else 2, trim=1 if trim else 2)
 
 
 def torch_dtype(name):
@@ -124,7 +104,8 @@ def run_share(grid, dims, n_steps=None, y_dtype="bf16", dx_dtype="bf16", backwar
     ws_d = [dev(b) for b in inp["w_blocks"]]
     bias_d = dev(inp["bias"])
     y = torch.empty((m, n), dtype=torch_dtype(y_dtype), device="cuda")
-    pre = torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
+    # an additive partial (1D row cut) takes no epilogue and saves no pre-activation
+    pre = None if inp["fwd"]["partial"] else torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
     say("  fwd: launching")
     T.tp_linear_fwd(grid, dims, inp["n_steps_fwd"], xs_d, ws_d, bias_d if epi != T.EPI_NONE else None, epi, y, pre, ws)
     torch.cuda.synchronize()
@@ -132,7 +113,8 @@ def run_share(grid, dims, n_steps=None, y_dtype="bf16", dx_dtype="bf16", backwar
     w64 = [f64(b) for b in inp["w_blocks"]]
     A, Y = O.share_fwd(x64, w64, f64(inp["bias"]) if epi != T.EPI_NONE else None, epi == T.EPI_BIAS_GELU, rows)
     check(host64(y[sel]), Y, y_dtype, "Y")
-    check(host64(pre[sel]), A, "bf16", "A_saved")
+    if pre is not None:
+        check(host64(pre[sel]), A, "bf16", "A_saved")
     del xs_d, ws_d, x64, w64
     if not backward:
         return

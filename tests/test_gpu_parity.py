@@ -32,12 +32,13 @@ SMALL = [
 
 @pytest.mark.parametrize("name,grid,dims", SMALL, ids=[s[0] for s in SMALL])
 def test_small_share_elementwise(name, grid, dims):
-    run_share(grid, dims, y_dtype="bf16", dx_dtype="bf16", want_db=True, label=name)
+    partial_dx = T.tp_block_map(grid, dims, T.PASS_DX)["partial"]       # a summand of a reduction: fp32 only
+    run_share(grid, dims, y_dtype="bf16", dx_dtype="f32" if partial_dx else "bf16", want_db=True, label=name)
     run_share(grid, dims, y_dtype="f32", dx_dtype="f32", label=name + " fp32 outputs", seed=77)
     run_share(grid, dims, y_dtype="f32", dx_dtype="f32", use_own_slot=False, label=name + " ready-made dA", seed=78)
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5])
 @pytest.mark.parametrize("split", [1, 3])
 def test_every_tile_shape_and_split(tile, split):
     grid, dims = T.Grid(T.MODE_2D, q=2, ri=0, rj=1), (2 * 300, 2 * 392, 2 * 328)
@@ -49,11 +50,8 @@ def test_k_rotation_off_and_other_group_heights():
     """The K-tile rotation and the tile-order group only change the order of work, never the result
     beyond fp32 summation order."""
     grid, dims = T.Grid(T.MODE_2D, q=2, ri=1, rj=1), (2 * 520, 2 * 1032, 2 * 776)
-    try:
-        T.tp_plan_override(3, 0)
+    with overrides(rotate=0):
         run_share(grid, dims, y_dtype="f32", dx_dtype="f32", label="rotation off")
-    finally:
-        T.tp_plan_override(3, 1)
     for group in (1, 7):
         with overrides(group=group):
             run_share(grid, dims, backward=False, label=f"group height {group}")
@@ -190,7 +188,9 @@ def test_seeded_random_shapes_and_grids():
                   want_db=bool(rng.integers(0, 2)), use_own_slot=bool(rng.integers(0, 2)))
         if mode == T.MODE_1D_ROW:
             kw.update(epi=T.EPI_NONE, backward=False, y_dtype="f32")      # the row-cut product is a partial sum: no epilogue
-        with overrides(tile=int(rng.integers(0, 5)), split=int(rng.integers(0, 4))):
+        if mode == T.MODE_1D_COL and p > 1:
+            kw.update(dx_dtype="f32")                                     # dX is a partial sum over the ranks: fp32 only
+        with overrides(tile=int(rng.integers(0, 6)), split=int(rng.integers(0, 4))):
             run_share(grid, dims, label=f"draw {case}", **kw)
 
 
@@ -444,7 +444,7 @@ def test_bwd_partials_small():
     _partials(T.Grid(T.MODE_2D, q=1), (257, 72, 8), label="q1: one product")
 
 
-@pytest.mark.parametrize("tile,split", [(1, 2), (2, 1), (3, 3), (4, 1), (4, 2)])
+@pytest.mark.parametrize("tile,split", [(1, 2), (2, 1), (3, 3), (4, 1), (4, 2), (5, 2)])
 def test_bwd_partials_tiles_and_split(tile, split):
     grid, dims = T.Grid(T.MODE_2D, q=3, ri=0, rj=2), (3 * 392, 3 * 264, 3 * 520)
     mx = T.tp_partials_map(grid, dims, T.PASS_DX_PARTIALS)

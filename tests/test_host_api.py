@@ -15,14 +15,23 @@ from paper_2110_14883_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "tp_linear.h")).read()
+def _declared(header):
+    hdr = open(os.path.join(ROOT, "include", header)).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    declared = set(re.findall(r"\b(tp_[a-z_0-9]+)\s*\(", hdr))
+    return set(re.findall(r"\b(tp_[a-z_0-9]+)\s*\(", hdr))
+
+
+def test_library_exports_every_declared_symbol():
+    declared = _declared("tp_linear.h")
     assert declared == set(B.EXPORTS)
     L = T.lib()
     for name in declared:
         assert getattr(L, name) is not None
+    # the measurement aid lives in a library of its own, not in the product ABI
+    assert not hasattr(L, "tp_mfma_probe") and not hasattr(L, "tp_plan_override")
+    probe = C.CDLL(os.path.join(ROOT, "paper_2110_14883_amd", "libtpprobe.so"))
+    for name in _declared("tp_probe.h"):
+        assert getattr(probe, name) is not None
 
 
 def test_strerror_texts():
@@ -192,10 +201,29 @@ def test_argument_errors_before_any_launch():
     assert _st(lambda: ba(cols=60)) == 5
     assert _st(lambda: ba(c=(0x10000, 56))) == 4
     assert _st(lambda: ba(pre=(0x50000, 64, B.DT_F32))) == 6
-    assert _st(lambda: T.tp_plan_override(9, 0)) == 2
-    assert _st(lambda: T.tp_plan_override(1, 99)) == 2
-    assert _st(lambda: T.tp_plan_override(0, 5)) == 2
-    T.tp_plan_override(3, 1)
+    # partial outputs: no epilogue, fp32 only (1D row cut forward; 1D column cut dX)
+    gr = T.Grid(T.MODE_1D_ROW, p=2)
+    fr = lambda **kw: T.tp_linear_fwd(gr, (256, 128, 256), 1, [(0x10000, 64)], [(0x30000, 256)], kw.get("bias", None),
+                                      kw.get("epi", T.EPI_NONE), kw.get("y", (0x20000, 256, B.DT_F32)), kw.get("pre", none_o), None, stream=0)
+    assert _st(lambda: fr(epi=T.EPI_BIAS, bias=0x40000)) == 2
+    assert _st(lambda: fr(pre=(0x50000, 256, B.DT_BF16))) == 2
+    assert _st(lambda: fr(y=(0x20000, 256, B.DT_BF16))) == 6
+    gc = T.Grid(T.MODE_1D_COL, p=2)
+    bc = lambda **kw: T.tp_linear_bwd(gc, (256, 128, 256), 1, 0, da_row_blocks=[(0x10000, 128)], w_blocks_dx=[(0x30000, 128)], stream=0, **kw)
+    assert _st(lambda: bc(dx=(0x60000, 128, B.DT_BF16))) == 6
+    assert _st(lambda: bc(dx=(0x60000, 128, B.DT_F32), dgelu_preact=(0x70000, 128))) == 2
+    # partials: output blocks of one call must not overlap
+    assert _st(lambda: pb(dxp=[(0x60000, 64, B.DT_F32), (0x60100, 64, B.DT_F32)])) == 4
+    # bias gradient
+    assert _st(lambda: T.tp_bias_grad((0, 64), 0x20000, 4, 64, stream=0)) == 1
+    assert _st(lambda: T.tp_bias_grad((0x10000, 64), 0, 4, 64, stream=0)) == 1
+    assert _st(lambda: T.tp_bias_grad((0x10000, 64), 0x20000, 4, 60, stream=0)) == 5
+    assert _st(lambda: T.tp_bias_grad((0x10000, 56), 0x20000, 4, 64, stream=0)) == 4
+    # plan options are validated like any other argument
+    for bad in (dict(tile=6), dict(split_k=9), dict(group_m=65), dict(rotate=3), dict(trim=-1)):
+        with T.plan_opts(**bad):
+            assert _st(lambda: call()) == 2
+            assert T.tp_linear_workspace_size(g, d, 0) == 0
 
 
 def test_workspace_size_bounds():
@@ -206,14 +234,24 @@ def test_workspace_size_bounds():
             ws = T.tp_linear_workspace_size(c.grid, c.dims, pass_)
             assert ws <= 8 * mp["m"] * mp["n"] * 4
     # trimming on or off, the bound holds
-    T.tp_plan_override(4, 0)
-    for c in WL.CONFIGS:
-        for pass_ in (0, 1, 2):
-            mp = T.tp_block_map(c.grid, c.dims, pass_)
-            assert T.tp_linear_workspace_size(c.grid, c.dims, pass_) <= 8 * mp["m"] * mp["n"] * 4
-    T.tp_plan_override(4, 1)
+    with T.plan_opts(trim=2):
+        for c in WL.CONFIGS:
+            for pass_ in (0, 1, 2):
+                mp = T.tp_block_map(c.grid, c.dims, pass_)
+                assert T.tp_linear_workspace_size(c.grid, c.dims, pass_) <= 8 * mp["m"] * mp["n"] * 4
     # a share with one output tile and a long contraction must split K
-    assert T.tp_linear_workspace_size(T.Grid(T.MODE_2D, q=1), (256, 65536, 256), 0) > 0
+    one_tile = (T.Grid(T.MODE_2D, q=1), (256, 65536, 256), 0)
+    assert T.tp_linear_workspace_size(*one_tile) > 0
+    # the query follows the plan options it is given: a forced split asks for exactly that many planes,
+    # and the options of another thread do not leak into this one
+    auto = T.tp_linear_workspace_size(*one_tile)
+    import threading
+    with T.plan_opts(split_k=3):
+        assert T.tp_linear_workspace_size(*one_tile) == 3 * 256 * 256 * 4
+        seen = []
+        th = threading.Thread(target=lambda: seen.append(T.tp_linear_workspace_size(*one_tile)))
+        th.start(); th.join()
+        assert seen[0] == auto
 
 
 def test_range_test_stored_bytes():
