@@ -107,8 +107,10 @@ void tp_gemm4_kernel(const GemmArgs p) {
     constexpr int TM = 4, TN = 4;                  // 32 x 32 MFMA tiles per wave along M and N
     // the transposed operand (if there is exactly one) is staged first: its reloads need the longer lead
     constexpr bool A_FIRST = A_KC ? B_KC : true;
-    // Both operands contraction-contiguous (the NT form): they go from memory to LDS directly.
-    constexpr bool DTL = A_KC && B_KC;
+    // A contraction-contiguous operand goes from memory to LDS directly: both operands of the NT form,
+    // operand A of the NN form (HYB: B then takes the register path with its transposes).
+    constexpr bool DA = A_KC, DB = A_KC && B_KC;
+    constexpr bool DTL = DA && DB, HYB = DA && !DB;
     static constexpr Slots SA = make_slots<A_KC, A_FIRST, B_KC>();
     static constexpr Slots SB = make_slots<B_KC, !A_FIRST, A_KC>();
 
@@ -198,6 +200,11 @@ void tp_gemm4_kernel(const GemmArgs p) {
     // differs between even and odd n by chunk ^ 2.
     u32x4_t rw_a, rw_b;
     uint32_t dl_a[2], dl_b[2], dv_a[2], dv_b[2];
+    // HYB: operand A is loaded one K tile behind the fetch cursor (its LDS stage is free only after the
+    // barrier, operand B's registers a tile earlier): these hold the cursor's previous descriptor and offsets
+    u32x4_t rw_l;
+    uint32_t dv_l[2];
+    int step_l;
     const int d_rl = w * 8 + (l >> 3);
     const int d_c0 = (l & 7) ^ ((d_rl >> 1) & 7) ^ (d_rl >> 4);
     const uint32_t s_wbase = (uint32_t)(w * 1024);
@@ -216,7 +223,7 @@ void tp_gemm4_kernel(const GemmArgs p) {
         __amdgpu_buffer_rsrc_t rs;
         uint32_t lane;
         int step, kmul;
-        if constexpr (KC && DTL) {
+        if constexpr (IS_A ? DA : DB) {
             const int64_t nrec = ok ? ((int64_t)(xs - 1) * ld + p.K) * 2 : 0;
             const uint64_t base = reinterpret_cast<uint64_t>(ptr + (int64_t)x0 * ld);
             const u32x4_t rw = {(uint32_t)uni((int)(uint32_t)base), (uint32_t)uni((int)((uint32_t)(base >> 32) & 0xffffu)),
@@ -251,19 +258,22 @@ void tp_gemm4_kernel(const GemmArgs p) {
         int kt = f.kt + f.rot;
         if (kt >= KT) kt -= KT;
         const int k0 = kt * BK;
-        if constexpr (DTL) {
+        if constexpr (DA || DB) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const bool kok = (k0 + (d_c0 ^ (2 * h)) * 8) < p.K;
-                dv_a[h] = kok ? dl_a[h] + (uint32_t)(k0 * 2) : OOB_OFFSET;
-                dv_b[h] = kok ? dl_b[h] + (uint32_t)(k0 * 2) : OOB_OFFSET;
+                if constexpr (DA) dv_a[h] = kok ? dl_a[h] + (uint32_t)(k0 * 2) : OOB_OFFSET;
+                if constexpr (DB) dv_b[h] = kok ? dl_b[h] + (uint32_t)(k0 * 2) : OOB_OFFSET;
             }
-            return;
         }
-        if constexpr (A_KC) va_off[Q] = (k0 + (t & 7) * 8) < p.K ? la_off + (uint32_t)(k0 * 2) : OOB_OFFSET;
-        else                va_off[Q] = la_off + (uint32_t)(k0 * a_kmul);
-        if constexpr (B_KC) vb_off[Q] = (k0 + (t & 7) * 8) < p.K ? lb_off + (uint32_t)(k0 * 2) : OOB_OFFSET;
-        else                vb_off[Q] = lb_off + (uint32_t)(k0 * b_kmul);
+        if constexpr (!DA) {
+            if constexpr (A_KC) va_off[Q] = (k0 + (t & 7) * 8) < p.K ? la_off + (uint32_t)(k0 * 2) : OOB_OFFSET;
+            else                va_off[Q] = la_off + (uint32_t)(k0 * a_kmul);
+        }
+        if constexpr (!DB) {
+            if constexpr (B_KC) vb_off[Q] = (k0 + (t & 7) * 8) < p.K ? lb_off + (uint32_t)(k0 * 2) : OOB_OFFSET;
+            else                vb_off[Q] = lb_off + (uint32_t)(k0 * b_kmul);
+        }
     };
     // Move the fetch cursor to the next K tile of the stream.  The common case (same C tile, same step)
     // is a few scalar instructions issued between two MFMAs; a change of step or of C tile needs other
@@ -292,9 +302,11 @@ void tp_gemm4_kernel(const GemmArgs p) {
     auto load1 = [&](auto is_a, auto n_, auto R_) __attribute__((always_inline)) {
         constexpr bool IS_A = decltype(is_a)::value;
         constexpr int n = decltype(n_)::value, R = decltype(R_)::value;
-        // (register set R is refilled while stage 1 - R is multiplied; the offsets of that K tile are copy 1 - R)
-        if constexpr (IS_A) sa[R][n] = buf_load16(rs_a, va_off[1 - R] + (uint32_t)(n * a_step));
-        else                sb[R][n] = buf_load16(rs_b, vb_off[1 - R] + (uint32_t)(n * b_step));
+        // (register set R is refilled while stage 1 - R is multiplied; the offsets of that K tile are copy
+        // 1 - R, or the one copy there is when the cursor moves before the loads of a body instead of after)
+        constexpr int Q = HYB ? 0 : 1 - R;
+        if constexpr (IS_A) sa[R][n] = buf_load16(rs_a, va_off[Q] + (uint32_t)(n * a_step));
+        else                sb[R][n] = buf_load16(rs_b, vb_off[Q] + (uint32_t)(n * b_step));
     };
     // n-th direct-to-LDS load of an operand into stage S
     auto dtl1 = [&](auto is_a, auto n_, auto S_) __attribute__((always_inline)) {
@@ -303,6 +315,11 @@ void tp_gemm4_kernel(const GemmArgs p) {
         constexpr uint32_t dst = (IS_A ? 0u : (uint32_t)W4_B_BASE) + decltype(S_)::value * W4_STAGE_STRIDE + n * 4096;
         if constexpr (IS_A) dtl_load16(rw_a, dv_a[n & 1] + (uint32_t)(n * a_step), s_wbase + dst);
         else                dtl_load16(rw_b, dv_b[n & 1] + (uint32_t)(n * b_step), s_wbase + dst);
+    };
+    auto dtl1_lag = [&](auto n_, auto S_) __attribute__((always_inline)) {       // operand A, one K tile behind the cursor
+        constexpr int n = decltype(n_)::value;
+        constexpr uint32_t dst = decltype(S_)::value * W4_STAGE_STRIDE + n * 4096;
+        dtl_load16(rw_l, dv_l[n & 1] + (uint32_t)(n * step_l), s_wbase + dst);
     };
     // n-th LDS write of an operand from register set R into stage S.  A transposed operand's write is
     // row x + n of its 8 x 8 block: word wd = n / 2 of the eight loaded rows, low or high halves, formed
@@ -379,7 +396,10 @@ void tp_gemm4_kernel(const GemmArgs p) {
                 // every LDS write of this K tile was issued before here; after the barrier the other
                 // stage is complete, and nobody reads the current one any more (the step-3 fragments
                 // were requested during step 2 and have arrived: the barrier waits for them)
-                if constexpr (DTL) wait_vm<0>();    // this wave's direct-to-LDS loads of the next K tile have landed
+                // this wave's direct-to-LDS loads of the next K tile have landed (HYB: all but this body's
+                // eight register loads, which are younger)
+                if constexpr (DTL) wait_vm<0>();
+                if constexpr (HYB) wait_vm<8>();
                 __syncthreads();
             }
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks & 1][j], fa[ks & 1][i], acc[i][j], 0, 0, 0);
@@ -402,7 +422,25 @@ void tp_gemm4_kernel(const GemmArgs p) {
                 if constexpr (s == 40) { if (f_reopen) advance_slow(); }
                 if constexpr (s == 42) prep_tile(SW{});
             }
-            if constexpr (!DTL) static_for<8>([&](auto n_) __attribute__((always_inline)) {
+            if constexpr (HYB) {
+                // The cursor moves first (operand A's descriptor and offsets of the tile it leaves are kept:
+                // that tile's A loads come last in this body), then operand B: out of its registers into the
+                // stage being refilled, and the cursor's K tile into those registers.
+                if constexpr (s == 2) {
+                    rw_l = rw_a; step_l = a_step; dv_l[0] = dv_a[0]; dv_l[1] = dv_a[1];
+                    advance_fast();
+                }
+                if constexpr (s == 4) { if (f_reopen) advance_slow(); }
+                if constexpr (s == 6) prep_tile(std::integral_constant<int, 0>{});
+                static_for<8>([&](auto n_) __attribute__((always_inline)) {
+                    constexpr int n = decltype(n_)::value;
+                    if constexpr (SB.pm[n] == s) perm1(std::false_type{}, n_, SW{});
+                    if constexpr (SB.wr[n] == s) store1(std::false_type{}, n_, SW{}, SW{});
+                    if constexpr (SB.ld[n] == s) load1(std::false_type{}, n_, SW{});
+                });
+                if constexpr ((s & 1) == 1 && s > 48) dtl1_lag(std::integral_constant<int, (s - 49) / 2>{}, SR{});
+            }
+            if constexpr (!DA) static_for<8>([&](auto n_) __attribute__((always_inline)) {
                 constexpr int n = decltype(n_)::value;
                 if constexpr (!A_KC && SA.pm[n] == s) perm1(std::true_type{}, n_, SW{});
                 if constexpr (!B_KC && SB.pm[n] == s) perm1(std::false_type{}, n_, SW{});
@@ -413,11 +451,11 @@ void tp_gemm4_kernel(const GemmArgs p) {
             });
             // the fetch cursor moves on to the K tile the NEXT body loads, and that tile's lane offsets go
             // into the other copy; descriptors stay as they are until this tile's last load has been issued
-            if constexpr (!DTL && s == 3) advance_fast();
-            if constexpr (!DTL && s == 9) prep_tile(SW{});
+            if constexpr (!DA && s == 3) advance_fast();
+            if constexpr (!DA && s == 9) prep_tile(SW{});
             __builtin_amdgcn_sched_barrier(0);
         });
-        if constexpr (!DTL) {
+        if constexpr (!DA) {
             if (f_reopen) {
                 advance_slow();
                 prep_tile(SW{});
@@ -427,6 +465,11 @@ void tp_gemm4_kernel(const GemmArgs p) {
 
     // ------------------------------------------------------------------ epilogue of the compute cursor's C tile
     // acc[i][j][e]: row m = 32 i + lane%32, columns n = 32 j + 8 (e/4) + 4 (lane/32) + e%4.
+    // No branch depends on a lane: every global access goes through a buffer descriptor that starts at
+    // the first row of this wave's 128 x 128 block and ends with the last row of the matrix, so rows
+    // below a ragged edge are dropped by the range check, and a lane whose columns lie beyond N carries
+    // an out-of-range offset.  One slab = 32 rows x 128 columns passes through the wave's LDS patch so
+    // that stores are whole row segments.
     auto epilogue = [&]() __attribute__((always_inline)) {
         const int m_sub = c.m0 + wm * 128, n_sub = c.n0 + wn * 128;
         const int r = lr;
@@ -435,17 +478,51 @@ void tp_gemm4_kernel(const GemmArgs p) {
         constexpr bool use_gelu = EPI == EPI_BIAS_GELU;
         constexpr bool use_dg = EPI == EPI_MUL_DGELU;
         const bool use_pre = !use_dg && p.pre != nullptr;
+        const int rows_left = p.M - m_sub;
+        // rows m_sub .. M - 1 of a matrix with leading dimension ld (elements of es bytes), N columns
+        auto block_rsrc = [&](const void* base, int64_t ld, int es) __attribute__((always_inline)) {
+            const int64_t nrec = rows_left > 0 ? ((int64_t)(rows_left - 1) * ld + p.N) * es : 0;
+            return make_rsrc(uni_ptr(static_cast<const char*>(base) + (int64_t)m_sub * ld * es), nrec);
+        };
+        u32x2_t bias_v[TN][4];
+        if constexpr (use_bias) {
+            const __amdgpu_buffer_rsrc_t rs_bias = make_rsrc(uni_ptr(p.bias), (int64_t)p.N * 2);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const u32x2_t b = __builtin_amdgcn_raw_buffer_load_b64(rs_bias, (n_sub + 32 * j + 8 * g + 4 * ch) * 2, 0, 0);
+                    bias_v[j][g] = b;
+                }
+        }
+        __amdgpu_buffer_rsrc_t rs_dg;
+        uint32_t dg_lane = 0;
+        if constexpr (use_dg) {
+            rs_dg = block_rsrc(p.dg, p.lddg, 2);
+            dg_lane = (uint32_t)((r * (int)p.lddg + n_sub + 4 * ch) * 2);   // columns past N: the next row's values or zeros, never stored
+        }
+        // The accumulators stay where the MFMAs keep them (the accumulator half of the register file) and
+        // are fetched four at a time, where they are used: left to itself the compiler copies all 256 out
+        // at once, which cannot fit beside the staging registers.
         auto raw4 = [&](int i, int j, int g, float (&v)[4]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * g + e];
+            for (int e = 0; e < 4; ++e) asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v[e]) : "a"(acc[i][j][4 * g + e]));
         };
         auto preact4 = [&](int i, int j, int g, float (&v)[4]) __attribute__((always_inline)) {
             raw4(i, j, g, v);
             if constexpr (use_bias) {
-                const int n = n_sub + 32 * j + 8 * g + 4 * ch;
-                u32x2_t b = {0u, 0u};
-                if (n < p.N) b = *reinterpret_cast<const u32x2_t*>(static_cast<const uint16_t*>(p.bias) + n);
+                const u32x2_t b = bias_v[j][g];
                 v[0] += bf16_lo(b[0]); v[1] += bf16_hi(b[0]); v[2] += bf16_lo(b[1]); v[3] += bf16_hi(b[1]);
+            }
+        };
+        u32x2_t dg_v[TN][4];
+        auto load_dg = [&](int i) __attribute__((always_inline)) {
+            if constexpr (use_dg) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        dg_v[j][g] = __builtin_amdgcn_raw_buffer_load_b64(rs_dg, dg_lane + (uint32_t)(((32 * i) * (int)p.lddg + 32 * j + 8 * g) * 2), 0, 0);
             }
         };
         auto final4 = [&](int i, int j, int g, float (&v)[4]) __attribute__((always_inline)) {
@@ -455,17 +532,16 @@ void tp_gemm4_kernel(const GemmArgs p) {
                 for (int e = 0; e < 4; ++e) v[e] = gelu_f(v[e]);
             }
             if constexpr (use_dg) {
-                const int m = m_sub + 32 * i + r, n = n_sub + 32 * j + 8 * g + 4 * ch;
-                if (m < p.M && n < p.N) {
-                    const u32x2_t a = *reinterpret_cast<const u32x2_t*>(static_cast<const uint16_t*>(p.dg) + (int64_t)m * p.lddg + n);
-                    v[0] *= dgelu_f(bf16_lo(a[0])); v[1] *= dgelu_f(bf16_hi(a[0]));
-                    v[2] *= dgelu_f(bf16_lo(a[1])); v[3] *= dgelu_f(bf16_hi(a[1]));
-                }
+                const u32x2_t a = dg_v[j][g];
+                v[0] *= dgelu_f(bf16_lo(a[0])); v[1] *= dgelu_f(bf16_hi(a[0]));
+                v[2] *= dgelu_f(bf16_lo(a[1])); v[3] *= dgelu_f(bf16_hi(a[1]));
             }
         };
         // bf16 slab of 32 rows x 128 columns: rows of 256 bytes in the patch; a lane writes 8 bytes and
-        // reads back 16 (chunk index XOR row keeps both conflict-free), stores are 256-byte row segments
-        auto slab_bf16 = [&](int i, auto value4, uint16_t* base, int64_t ld) __attribute__((always_inline)) {
+        // reads back 16 (chunk index XOR row keeps both conflict-free), stores are 256-byte row segments:
+        // lane l stores columns 8 (l % 16) .. + 7 of rows l / 16 + 4 it
+        auto slab_bf16 = [&](int i, auto value4, __amdgpu_buffer_rsrc_t rs, int ld) __attribute__((always_inline)) {
+            const uint32_t lane = (n_sub + 8 * (l & 15)) < p.N ? (uint32_t)(((l >> 4) * ld + n_sub + 8 * (l & 15)) * 2) : OOB_OFFSET;
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -479,14 +555,16 @@ void tp_gemm4_kernel(const GemmArgs p) {
             for (int it = 0; it < 8; ++it) {
                 const int rr = it * 4 + (l >> 4), cc = l & 15;
                 const u32x4_t v = *reinterpret_cast<const u32x4_t*>(eps + rr * 256 + ((cc ^ (rr & 15)) << 4));
-                const int m = m_sub + 32 * i + rr, n = n_sub + 8 * cc;
-                if (m < p.M && n < p.N) *reinterpret_cast<u32x4_t*>(base + (int64_t)m * ld + n) = v;
+                __builtin_amdgcn_raw_buffer_store_b128(v, rs, (int)(lane + (uint32_t)((32 * i + 4 * it) * ld * 2)), 0, 0);
             }
         };
-        // fp32 slab, one 32-column block at a time: rows of 128 bytes
-        auto slab_f32 = [&](int i, auto value4, float* base, int64_t ld) __attribute__((always_inline)) {
+        // fp32 slab, one 32-column block at a time: rows of 128 bytes; lane l stores columns
+        // 4 (l % 8) .. + 3 of rows l / 8 + 8 it
+        auto slab_f32 = [&](int i, auto value4, __amdgpu_buffer_rsrc_t rs, int ld) __attribute__((always_inline)) {
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
+                const int n = n_sub + 32 * j + 4 * (l & 7);
+                const uint32_t lane = n < p.N ? (uint32_t)(((l >> 3) * ld + n) * 4) : OOB_OFFSET;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     float x[4];
@@ -497,29 +575,40 @@ void tp_gemm4_kernel(const GemmArgs p) {
 #pragma unroll
                 for (int it = 0; it < 4; ++it) {
                     const int rr = it * 8 + (l >> 3), cc = l & 7;
-                    const f32x4_t v = *reinterpret_cast<const f32x4_t*>(eps + rr * 128 + ((cc ^ ((rr >> 1) & 7)) << 4));
-                    const int m = m_sub + 32 * i + rr, n = n_sub + 32 * j + 4 * cc;
-                    if (m < p.M && n < p.N) *reinterpret_cast<f32x4_t*>(base + (int64_t)m * ld + n) = v;
+                    const u32x4_t v = *reinterpret_cast<const u32x4_t*>(eps + rr * 128 + ((cc ^ ((rr >> 1) & 7)) << 4));
+                    __builtin_amdgcn_raw_buffer_store_b128(v, rs, (int)(lane + (uint32_t)((32 * i + 8 * it) * ld * 4)), 0, 0);
                 }
             }
         };
         // The loads of the K tile after next are in flight.  Loads and stores complete out of order
         // with respect to each other, so a wait for those loads issued after the first store would
         // have to wait for every store as well: take the loads in before the first store instead.
-        // (Direct-to-LDS loads feed no register: nothing to take in.)
-        if constexpr (!DTL) wait_vm<0>();
+        // (Direct-to-LDS loads feed no register: nothing to take in; HYB issued eight of them last.)
+        if constexpr (HYB) wait_vm<8>();
+        else if constexpr (!DTL) wait_vm<0>();
+        // (the last MFMA's result is read by hand-placed instructions: give it the 19 cycles it needs)
+        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
         if (partial) {
-            float* const wsz = p.ws + ((int64_t)c.z * p.n_groups + c.g) * p.M * p.N;
-#pragma unroll
-            for (int i = 0; i < TM; ++i) slab_f32(i, raw4, wsz, (int64_t)p.N);
-        } else {
+            const __amdgpu_buffer_rsrc_t rs_ws = block_rsrc(p.ws + ((int64_t)c.z * p.n_groups + c.g) * p.M * p.N, (int64_t)p.N, 4);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
+                slab_f32(i, raw4, rs_ws, p.N);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+            const int ldo = (int)p.ldos[c.g];
+            const __amdgpu_buffer_rsrc_t rs_out = block_rsrc(p.outs[c.g], ldo, F32_OUT ? 4 : 2);
+            __amdgpu_buffer_rsrc_t rs_pre;
+            if constexpr (!use_dg) rs_pre = block_rsrc(p.pre, p.ldp, 2);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                load_dg(i);
                 if constexpr (!use_dg) {
-                    if (use_pre) slab_bf16(i, preact4, static_cast<uint16_t*>(p.pre), p.ldp);
+                    if (use_pre) slab_bf16(i, preact4, rs_pre, (int)p.ldp);
                 }
-                if constexpr (F32_OUT) slab_f32(i, final4, static_cast<float*>(p.outs[c.g]), p.ldos[c.g]);
-                else                   slab_bf16(i, final4, static_cast<uint16_t*>(p.outs[c.g]), p.ldos[c.g]);
+                if constexpr (F32_OUT) slab_f32(i, final4, rs_out, ldo);
+                else                   slab_bf16(i, final4, rs_out, ldo);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     };
@@ -552,6 +641,23 @@ void tp_gemm4_kernel(const GemmArgs p) {
         move_on(S0{});
         static_for<8>([&](auto n_) __attribute__((always_inline)) { dtl1(std::true_type{}, n_, S1{}); });
         wait_vm<8>();
+    } else if constexpr (HYB) {
+        // K tile 0: A -> stage 0, B -> register set 0 -> stage 0;  K tile 1: A -> stage 1, B -> set 1;
+        // K tile 2: B -> set 0 (its A is the first body's business).  The cursor stays on K tile 2.
+        using Q0 = std::integral_constant<int, 0>;
+        prep_tile(Q0{});
+        static_for<8>([&](auto n_) __attribute__((always_inline)) { dtl1(std::true_type{}, n_, S0{}); });
+        static_for<8>([&](auto n_) __attribute__((always_inline)) { load1(std::false_type{}, n_, S0{}); });
+        move_on(Q0{});
+        static_for<8>([&](auto n_) __attribute__((always_inline)) { dtl1(std::true_type{}, n_, S1{}); });
+        static_for<8>([&](auto n_) __attribute__((always_inline)) { load1(std::false_type{}, n_, S1{}); });
+        static_for<8>([&](auto n_) __attribute__((always_inline)) {
+            perm1(std::false_type{}, n_, S0{});
+            store1(std::false_type{}, n_, S0{}, S0{});
+        });
+        move_on(Q0{});
+        static_for<8>([&](auto n_) __attribute__((always_inline)) { load1(std::false_type{}, n_, S0{}); });
+        wait_vm<24>();                             // operand A of K tile 0 is the oldest of the 40 loads
     } else {
     prep_tile(S1{});
     load_all(S0{});                                // (set 0 takes its offsets from copy 1, set 1 from copy 0)
