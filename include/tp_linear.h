@@ -50,7 +50,8 @@ typedef enum {
     TP_ERR_ALIGN = 5,      /* pointer not 16-byte aligned, or ld / column extent not a multiple of 8 */
     TP_ERR_DTYPE = 6,      /* output dtype not supported for this output */
     TP_ERR_WORKSPACE = 7,  /* workspace NULL or smaller than tp_linear_workspace_size() says */
-    TP_ERR_HIP = 8         /* a HIP call (launch) reported an error */
+    TP_ERR_HIP = 8,        /* a HIP call (launch) reported an error */
+    TP_ERR_SCRATCH = 9     /* tp_linear_fwd_static: the product needs more than the built-in scratch */
 } tp_status_t;
 
 /* Partition modes.  The 1D scheme is two modes because its two weights are cut differently. */
@@ -154,6 +155,27 @@ int tp_linear_fwd_ex(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps,
                      const tp_cblk_t* x_blocks, const tp_cblk_t* w_blocks,
                      const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact,
                      void* workspace, size_t workspace_bytes, void* hip_stream, const tp_plan_opts_t* opts);
+
+/*
+ * tp_linear_fwd_static -- tp_linear_fwd for callers that cannot allocate device memory and have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same checks and the same result as tp_linear_fwd with default plan
+ * options, minus the workspace: the fp32 partial planes of a K-split product go to a fixed array of
+ * tp_static_scratch_bytes() = 64 MiB that is part of the library's device image (each GPU the library
+ * runs on holds its own copy until the process ends).  The call allocates and frees nothing; the
+ * first call on a device looks the array's address up once (not capturable: make one call on the
+ * device before capturing).  A product whose planes need more than the array is refused with
+ * TP_ERR_SCRATCH and nothing is launched.  All calls on one GPU share the array: calls that may
+ * overlap in time on one GPU (different streams, different threads) race on it and must be ordered
+ * by the caller.  Nothing in the array has to start at zero: every partial the fix-up pass reads
+ * was written by the product kernel of the same call.
+ * Errors: those of tp_linear_fwd except TP_ERR_WORKSPACE, plus TP_ERR_SCRATCH.
+ */
+int tp_linear_fwd_static(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps,
+                         const tp_cblk_t* x_blocks, const tp_cblk_t* w_blocks,
+                         const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact, void* hip_stream);
+/* Size in bytes of the built-in scratch array of tp_linear_fwd_static (host only, no GPU call). */
+size_t tp_static_scratch_bytes(void);
 
 /*
  * tp_linear_bwd -- backward share.  In order, each part only if its outputs are wanted:

@@ -112,6 +112,10 @@ def lib() -> C.CDLL:
         L.tp_linear_fwd.argtypes = fwd_args
         L.tp_linear_fwd_ex.restype = C.c_int
         L.tp_linear_fwd_ex.argtypes = fwd_args + [po]
+        L.tp_linear_fwd_static.restype = C.c_int
+        L.tp_linear_fwd_static.argtypes = fwd_args[:9] + [C.c_void_p]
+        L.tp_static_scratch_bytes.restype = C.c_size_t
+        L.tp_static_scratch_bytes.argtypes = []
         L.tp_linear_bwd.restype = C.c_int
         L.tp_linear_bwd.argtypes = bwd_args
         L.tp_linear_bwd_ex.restype = C.c_int
@@ -138,7 +142,8 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("tp_block_map", "tp_linear_workspace_size", "tp_linear_workspace_size_ex", "tp_linear_fwd", "tp_linear_fwd_ex",
            "tp_linear_bwd", "tp_linear_bwd_ex", "tp_dgelu", "tp_partials_map", "tp_linear_bwd_partials",
-           "tp_linear_bwd_partials_ex", "tp_bias_act", "tp_bias_grad", "tp_strerror")
+           "tp_linear_bwd_partials_ex", "tp_bias_act", "tp_bias_grad", "tp_strerror", "tp_linear_fwd_static",
+           "tp_static_scratch_bytes")
 
 
 # ----------------------------------------------------------------------------- marshalling helpers
@@ -264,6 +269,20 @@ def tp_linear_fwd(grid: Grid, dims, n_steps: int, x_blocks, w_blocks, bias, epi:
                                 _cblk_array(w_blocks, n_steps), _ptr(bias), int(epi), _oblk(y), _oblk(preact),
                                 ws, wsb, _stream(stream), _opts())
     _check(st, "tp_linear_fwd")
+
+
+def tp_linear_fwd_static(grid: Grid, dims, n_steps: int, x_blocks, w_blocks, bias, epi: int, y, preact=None,
+                         stream=None) -> None:
+    """tp_linear_fwd without a workspace: K-split partials go to the library's built-in scratch array."""
+    g, d = grid._c(), _dims(dims)
+    st = lib().tp_linear_fwd_static(C.byref(g), C.byref(d), int(n_steps), _cblk_array(x_blocks, n_steps),
+                                    _cblk_array(w_blocks, n_steps), _ptr(bias), int(epi), _oblk(y), _oblk(preact),
+                                    _stream(stream))
+    _check(st, "tp_linear_fwd_static")
+
+
+def tp_static_scratch_bytes() -> int:
+    return int(lib().tp_static_scratch_bytes())
 
 
 def tp_linear_bwd(grid: Grid, dims, n_steps_dx: int = 0, n_steps_dw: int = 0, dy_own=None, preact_own=None,

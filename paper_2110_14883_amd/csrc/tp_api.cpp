@@ -280,6 +280,16 @@ bool w4_eligible(int form, const GemmArgs& a) {
         if (a_kc ? (255 * lda + K) * 2 >= ((int64_t)1 << 31) : (K * lda + 256) * 2 >= ((int64_t)1 << 31)) return false;
         if (b_kc ? (255 * ldb + K) * 2 >= ((int64_t)1 << 31) : (K * ldb + 256) * 2 >= ((int64_t)1 << 31)) return false;
     }
+    // its epilogue addresses a wave's 128 rows of every output (and of the GeLU' operand) the same way
+    const int64_t lim = (int64_t)1 << 31, N = a.N;
+    const int groups = a.n_groups > 1 ? a.n_groups : 1;
+    for (int g = 0; g < groups; ++g) {
+        const int64_t ldo = a.n_groups > 1 ? a.ldos[g] : a.ldo;
+        if ((128 * ldo + N) * 4 >= lim) return false;
+    }
+    if (a.pre && (128 * a.ldp + N) * 2 >= lim) return false;
+    if (a.dg && (128 * a.lddg + N) * 2 >= lim) return false;
+    if (129 * N * 4 >= lim) return false;          // split-K planes
     return true;
 }
 
@@ -344,6 +354,81 @@ Range out_range(const tp_oblk_t& b, int64_t rows, int64_t cols) {
 }
 bool overlap(const Range& a, const Range& b) { return a.lo < b.hi && b.lo < a.hi; }
 
+// ---------------------------------------------------------------------------------------------
+// Built-in scratch for tp_linear_fwd_static: a fixed array in device memory (every GPU the library
+// runs on holds its own copy until the process ends).  Host code never uses the array's name as an
+// address: the address on the current device is asked for once per device and kept.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+int static_scratch(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TP_ERR_HIP;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TP_ERR_HIP;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);      // (two threads racing here store the same address)
+    }
+    *out = ptr;
+    return TP_OK;
+}
+
+int linear_fwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps, const tp_cblk_t* x_blocks,
+               const tp_cblk_t* w_blocks, const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact,
+               void* workspace, size_t workspace_bytes, void* hip_stream, const tp_plan_opts_t* opts,
+               bool use_static_scratch) {
+    Opts o;
+
+    if (int e = resolve_opts(opts, &o)) return e;
+    Share s;
+    if (int e = build_share(grid, dims, TP_PASS_FWD, &s)) return e;
+    if (!x_blocks || !w_blocks) return TP_ERR_NULL;
+    if (n_steps < 1 || n_steps > s.n_steps) return TP_ERR_SHAPE;
+    if (epi != TP_EPI_NONE && epi != TP_EPI_BIAS && epi != TP_EPI_BIAS_GELU) return TP_ERR_MODE;
+    if (epi != TP_EPI_NONE && !bias) return TP_ERR_NULL;
+    if (bias && !aligned16(bias)) return TP_ERR_ALIGN;
+    if (s.partial) {                    // an additive partial: bias and GeLU come after the summation
+        if (epi != TP_EPI_NONE || preact.ptr) return TP_ERR_MODE;
+        if (y.ptr && y.dtype != TP_F32) return TP_ERR_DTYPE;
+    }
+    if (s.m > INT32_MAX || s.n > INT32_MAX || s.k > INT32_MAX) return TP_ERR_SHAPE;
+    for (int k = 0; k < n_steps; ++k) {
+        if (int e = check_cblk(x_blocks[k], s.k)) return e;
+        if (int e = check_cblk(w_blocks[k], s.n)) return e;
+    }
+    if (int e = check_oblk(y, s.n, false)) return e;
+    if (preact.ptr) {
+        if (int e = check_oblk(preact, s.n, false)) return e;
+        if (preact.dtype != TP_BF16) return TP_ERR_DTYPE;
+    }
+    Plan p = make_plan(o, s.m, s.n, s.k, n_steps);
+    if (use_static_scratch) {
+        if (ws_bytes_for(p, s.m, s.n) > kStaticScratchBytes) return TP_ERR_SCRATCH;
+    } else if (!ws_ok(ws_bytes_for(p, s.m, s.n), workspace, workspace_bytes)) {
+        return TP_ERR_WORKSPACE;
+    }
+    if (int e = check_device()) return e;
+    if (use_static_scratch) {
+        if (int e = static_scratch(&workspace)) return e;
+    }
+
+    Product pr{};
+    pr.form = FORM_NN; pr.plan = p;
+    fill_common(o, pr.args, p, s.m, s.n, s.k, n_steps);
+    for (int k = 0; k < n_steps; ++k) {
+        pr.args.a[k] = x_blocks[k].ptr; pr.args.lda[k] = (int32_t)x_blocks[k].ld;
+        pr.args.b[k] = w_blocks[k].ptr; pr.args.ldb[k] = (int32_t)w_blocks[k].ld;
+    }
+    pr.args.out = y.ptr; pr.args.ldo = y.ld; pr.args.out_f32 = y.dtype == TP_F32;
+    pr.args.pre = preact.ptr; pr.args.ldp = preact.ld;
+    pr.args.bias = epi == TP_EPI_NONE ? nullptr : bias;
+    pr.args.gelu = epi == TP_EPI_BIAS_GELU;
+    return run_product(o, pr, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
 }  // namespace
 
 extern "C" {
@@ -395,46 +480,17 @@ size_t tp_linear_workspace_size(const tp_grid_t* grid, const tp_dims_t* dims, in
 int tp_linear_fwd_ex(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps, const tp_cblk_t* x_blocks,
                      const tp_cblk_t* w_blocks, const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact,
                      void* workspace, size_t workspace_bytes, void* hip_stream, const tp_plan_opts_t* opts) {
-    Opts o;
-    if (int e = resolve_opts(opts, &o)) return e;
-    Share s;
-    if (int e = build_share(grid, dims, TP_PASS_FWD, &s)) return e;
-    if (!x_blocks || !w_blocks) return TP_ERR_NULL;
-    if (n_steps < 1 || n_steps > s.n_steps) return TP_ERR_SHAPE;
-    if (epi != TP_EPI_NONE && epi != TP_EPI_BIAS && epi != TP_EPI_BIAS_GELU) return TP_ERR_MODE;
-    if (epi != TP_EPI_NONE && !bias) return TP_ERR_NULL;
-    if (bias && !aligned16(bias)) return TP_ERR_ALIGN;
-    if (s.partial) {                    // an additive partial: bias and GeLU come after the summation
-        if (epi != TP_EPI_NONE || preact.ptr) return TP_ERR_MODE;
-        if (y.ptr && y.dtype != TP_F32) return TP_ERR_DTYPE;
-    }
-    if (s.m > INT32_MAX || s.n > INT32_MAX || s.k > INT32_MAX) return TP_ERR_SHAPE;
-    for (int k = 0; k < n_steps; ++k) {
-        if (int e = check_cblk(x_blocks[k], s.k)) return e;
-        if (int e = check_cblk(w_blocks[k], s.n)) return e;
-    }
-    if (int e = check_oblk(y, s.n, false)) return e;
-    if (preact.ptr) {
-        if (int e = check_oblk(preact, s.n, false)) return e;
-        if (preact.dtype != TP_BF16) return TP_ERR_DTYPE;
-    }
-    Plan p = make_plan(o, s.m, s.n, s.k, n_steps);
-    if (!ws_ok(ws_bytes_for(p, s.m, s.n), workspace, workspace_bytes)) return TP_ERR_WORKSPACE;
-    if (int e = check_device()) return e;
-
-    Product pr{};
-    pr.form = FORM_NN; pr.plan = p;
-    fill_common(o, pr.args, p, s.m, s.n, s.k, n_steps);
-    for (int k = 0; k < n_steps; ++k) {
-        pr.args.a[k] = x_blocks[k].ptr; pr.args.lda[k] = (int32_t)x_blocks[k].ld;
-        pr.args.b[k] = w_blocks[k].ptr; pr.args.ldb[k] = (int32_t)w_blocks[k].ld;
-    }
-    pr.args.out = y.ptr; pr.args.ldo = y.ld; pr.args.out_f32 = y.dtype == TP_F32;
-    pr.args.pre = preact.ptr; pr.args.ldp = preact.ld;
-    pr.args.bias = epi == TP_EPI_NONE ? nullptr : bias;
-    pr.args.gelu = epi == TP_EPI_BIAS_GELU;
-    return run_product(o, pr, workspace, static_cast<hipStream_t>(hip_stream));
+    return linear_fwd(grid, dims, n_steps, x_blocks, w_blocks, bias, epi, y, preact, workspace, workspace_bytes, hip_stream,
+                      opts, false);
 }
+
+int tp_linear_fwd_static(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps, const tp_cblk_t* x_blocks,
+                         const tp_cblk_t* w_blocks, const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact,
+                         void* hip_stream) {
+    return linear_fwd(grid, dims, n_steps, x_blocks, w_blocks, bias, epi, y, preact, nullptr, 0, hip_stream, nullptr, true);
+}
+
+size_t tp_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 int tp_linear_fwd(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps, const tp_cblk_t* x_blocks,
                   const tp_cblk_t* w_blocks, const void* bias, int epi, tp_oblk_t y, tp_oblk_t preact,
@@ -695,6 +751,7 @@ const char* tp_strerror(int status) {
         case TP_ERR_DTYPE: return "output dtype not supported here";
         case TP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case TP_ERR_HIP: return "a HIP call failed, or the device is not a 256-CU MI355X";
+        case TP_ERR_SCRATCH: return "the product needs more than the library's built-in scratch: call tp_linear_fwd with a workspace";
         default: return "unknown status";
     }
 }

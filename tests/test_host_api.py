@@ -273,3 +273,14 @@ def test_range_test_stored_bytes():
     # hidden 16384 on 8 GPUs: the paper measures 62 % (2.5D) and 74.2 % (3D) below 1D; the chunk count gives the same picture
     s1, s25, s3 = [R.stored_bytes(g, 32 * R.SEQ, 16384) for _, g in R.grids(8)]
     assert 0.55 < 1 - s25 / s1 < 0.75 and 0.70 < 1 - s3 / s1 < 0.85
+
+
+def test_static_entry_point_refuses_what_its_scratch_cannot_hold():
+    """tp_linear_fwd_static: a product whose K-split planes exceed the built-in array is refused before
+    anything touches the GPU (fake, aligned device addresses: nothing is dereferenced)."""
+    grid, dims = T.Grid(T.MODE_1D_COL, p=1), (2560, 262144, 4096)
+    assert T.tp_linear_workspace_size(grid, dims, T.PASS_FWD) > T.tp_static_scratch_bytes() == 64 << 20
+    m, k, n = dims
+    with pytest.raises(T.TpError) as e:
+        T.tp_linear_fwd_static(grid, dims, 1, [(0x10000, k)], [(0x20000, n)], None, T.EPI_NONE, (0x30000, n, B.DT_F32), stream=0)
+    assert e.value.status == 9 and "scratch" in str(e.value)
