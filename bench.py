@@ -5,16 +5,18 @@
 
 A step is one pass of the whole hot path of one rank's share (forward and backward, every
 product and elementwise kernel) over one batch of seeded synthetic blocks that are already
-resident in HBM.  The headline workload is the 1D (size 4) feed-forward share, M=16384, H=4096,
-F=16384 (six 16384 x 4096 x 4096 products); the other configurations are measured after it, each
-for a length chosen from its step time (>= 80 ms of warm-up, >= 250 ms timed: shorter runs sit in
-the power controller's settling transient), and reported under "per_config".  Prints ONE JSON line.
+resident in HBM.  The headline workload is the 3D (p = 2) share of the GPT-3-175B-shaped MLP, the
+largest of the five configurations: forward 4096 x 6144 x 24576 with bias and erf-GeLU, dA, dX and dW
+(3.71 TFLOP per step); the other configurations are measured after it, each for a length chosen
+from its step time (>= 80 ms of warm-up, >= 250 ms timed: shorter runs sit in the power controller's
+settling transient), and reported under "per_config".  Prints ONE JSON line.
 
 value       = GEMM flops of the step / wall time of the step (bf16 TFLOP/s, fp32 accumulation)
 roofline    = the dominant kernel (largest share of step time): its flops per launch / its average
               duration measured with HIP events on the launch stream, against the MI355X dense
               bf16 MFMA peak
-cpu_baseline= the fp64 oracle timed on the host cores on a bounded slab of the same share
+cpu_baseline= the fp64 oracle timed on the host cores on the same share (all of it when that is a
+              few seconds of BLAS-backed work, else a stated fraction of its token rows and dW rows)
 """
 from __future__ import annotations
 
@@ -50,7 +52,7 @@ def gemm_symbol(form: str, epi: int, f32_out: bool) -> str:
     """Name of the 256x256 GEMM instantiation a call launches (as rocprofv3 prints it, without
     'void' and the argument list).  form: NN / NT / TN; epi: 0 none, 1 bias, 2 bias+GeLU, 3 *GeLU'."""
     kc = {"NN": "true, false", "NT": "true, true", "TN": "false, false"}[form]
-    return f"tpl::tp_gemm_kernel<256, 256, {kc}, {epi}, {'true' if f32_out else 'false'}>"
+    return f"tpl::tp_gemm4_kernel<{kc}, {epi}, {'true' if f32_out else 'false'}>"
 
 
 def main() -> int:
@@ -58,7 +60,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--config", default="c2_1d_n4_mlp")
+    ap.add_argument("--config", default="c5_3d_p2")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--extra-steps", type=int, default=0,
@@ -393,7 +395,7 @@ def main() -> int:
         "value": main_res["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {cfg.note}", "dims_MHF": list(cfg.dims), "parallelism": "one rank's share, 1 GPU",
+        "config": {"workload": f"{cfg.name}: {cfg.note}", "parallelism": "one rank's share, 1 GPU",
                    "gemm_flops_per_step": main_res["gemm_flops"]},
         "pct_of_mfma_peak": main_res["pct_of_peak"],
         "roofline": roofline, "cpu_baseline": cpu, "calls": main_res["calls"], "per_config": extra,
@@ -404,7 +406,7 @@ def main() -> int:
 
 
 def cpu_baseline(cfg):
-    """The fp64 oracle, as it stands, on the host cores, on a slab of token rows of the same share."""
+    """The fp64 oracle, as it stands, on the host cores, on the same share."""
     import numpy as np
 
     import synth_inputs as S
@@ -432,7 +434,36 @@ def cpu_baseline(cfg):
         flops = 6 * 2.0 * rows * H * inp["fb"]
         sample = f"all six products of the same rank share, {rows} of {M} token rows"
     else:
-        raise NotImplementedError("CPU baseline is timed on the headline 1D workload")
+        # owner-computes share: forward (+ bias, GeLU), own dA, dX over the row's dA blocks, dW over the
+        # column's.  The peers' dA blocks are inputs (as on the GPU), made before the clock starts.
+        # Bounded to about 6 TFLOP of fp64 work (10 - 30 s on a GPU machine's host share) by taking the first `rows` token rows of the share
+        # (dW's contraction then runs over those rows only: the same arithmetic, a slab of the sum).
+        inp = WL.make_share_inputs(cfg.grid, cfg.dims, S.BASE_SEED, cfg.n_steps, cfg.backward)
+        m, n, k, sf = inp["m"], inp["n"], inp["k"], inp["n_steps_fwd"]
+        one = 2.0 * m * n * k * sf
+        nprod = 3 if cfg.backward else 1
+        rows = max(1, min(m, int(m * 6.0e12 / (one * nprod))))
+        rsel = slice(0, rows)
+        xb = [O.bf16_bits_to_f64(b[rsel]) for b in inp["x_blocks"]]
+        wb = [O.bf16_bits_to_f64(b) for b in inp["w_blocks"]]
+        bias = O.bf16_bits_to_f64(inp["bias"])
+        if cfg.backward:
+            g_own = O.bf16_bits_to_f64(inp["g_own"][rsel])
+            wdx = [O.bf16_bits_to_f64(b) for b in inp["w_blocks_dx"]]
+            xdw = [O.bf16_bits_to_f64(b[rsel]) for b in inp["x_blocks_dw"]]
+            peer = lambda pr: O.share_da(O.bf16_bits_to_f64(pr[0][rsel]), O.bf16_bits_to_f64(pr[1][rsel]))
+            peers_dx = {i: peer(pr) for i, pr in inp["peers_dx"].items()}
+            peers_dw = {i: peer(pr) for i, pr in inp["peers_dw"].items()}
+        t0 = time.perf_counter()
+        A, _ = O.share_fwd(xb, wb, bias, act=True)
+        if cfg.backward:
+            dA = O.share_da(g_own, O.round_to_bf16(A))
+            O.share_dx([dA if i == inp["own_slot_dx"] else peers_dx[i] for i in range(inp["n_steps_dx"])], wdx)
+            O.share_dw(xdw, [dA if i == inp["own_slot_dw"] else peers_dw[i] for i in range(inp["n_steps_dw"])])
+        dt = time.perf_counter() - t0
+        flops = nprod * one * rows / m
+        sample = (f"the first {rows} of {m} token rows of the same rank share: forward with bias and GeLU, own dA, dX, "
+                  f"and dW summed over those rows" if cfg.backward else f"the first {rows} of {m} token rows of the forward share")
     log(f"[bench] cpu oracle: {flops / dt / 1e9:.1f} GFLOP/s fp64 on {cores} threads ({dt:.1f}s)")
     return dict(value=round(flops / dt / 1e12, 4), unit="TFLOP/s", cores=cores, kind="oracle", sample=sample,
                 seconds=round(dt, 2), dtype="f64")

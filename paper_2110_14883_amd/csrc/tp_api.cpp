@@ -163,6 +163,14 @@ struct Plan {
     int tail_tile_id, tail_tiles_m, tail_tiles_n, tail_split;
 };
 
+// Measured costs in shader cycles.  One 64-deep K tile of one workgroup: the four-wave stream kernel
+// (256 x 256) takes 2500 - 2900 against 2048 of pure MFMA issue; the eight-wave kernel's half and
+// quarter tiles move more bytes per flop and take ~2200 and ~1400.  On top of that every C tile has
+// a fixed cost: the epilogue alone for the stream kernel (its K tiles keep flowing across C tiles),
+// epilogue plus pipeline refill for the others.
+double k_tile_cycles(int bm, int bn) { return bm * bn == 65536 ? 2730.0 : (bm * bn == 32768 ? 2220.0 : 1410.0); }
+double c_tile_cycles(int bm, int bn) { return bm * bn == 65536 ? 12000.0 : 20000.0; }
+
 // Pick the macro-tile and the split of K so that the launch fills whole waves of the 256 CUs.
 // Cost model: (waves of workgroups) x (K tiles per workgroup) x (tile area), plus the fp32
 // round trip of the partials when K is split.
@@ -179,12 +187,8 @@ Plan plan_whole(const Opts& o, int64_t m, int64_t n, int64_t k, int n_steps, int
         tile_shape(tile_ids[ti], &bm, &bn);
         const int64_t tm = (m + bm - 1) / bm, tn = (n + bn - 1) / bn;
         const int64_t tiles = tm * tn * groups;
-        // cycles one workgroup spends on one 64-deep K tile (measured: ~1.8 us at ~1.8 GHz for
-        // 256x256); half and quarter tiles move more bytes per flop and measure ~1.3x / ~1.65x
-        // slower per flop; every C tile also costs a fixed ~11 us (epilogue, pipeline refill)
-        const double penalty = (bm == 256 && bn == 256) ? 1.0 : (bm == 128 && bn == 128 ? 1.65 : 1.3);
-        const double tile_cycles = (double)bm * bn * 64 * 2 / 4096.0 / 0.6 * penalty;
-        const double per_tile = 20000.0;
+        const double tile_cycles = k_tile_cycles(bm, bn);
+        const double per_tile = c_tile_cycles(bm, bn);
         for (int z = 1; z <= 8; ++z) {
             if (forced_split && z != forced_split) continue;
             if (z > T) break;
@@ -208,10 +212,7 @@ Plan plan_whole(const Opts& o, int64_t m, int64_t n, int64_t k, int n_steps, int
 }
 
 // cycles of one C tile of the given shape over T K tiles (the cost model's unit, see plan_whole)
-double tile_cost(int bm, int bn, int64_t T) {
-    const double penalty = (bm == 256 && bn == 256) ? 1.0 : (bm == 128 && bn == 128 ? 1.65 : 1.3);
-    return (double)T * ((double)bm * bn * 64 * 2 / 4096.0 / 0.6 * penalty) + 20000.0;
-}
+double tile_cost(int bm, int bn, int64_t T) { return (double)T * k_tile_cycles(bm, bn) + c_tile_cycles(bm, bn); }
 
 Plan make_plan(const Opts& o, int64_t m, int64_t n, int64_t k, int n_steps, int groups = 1) {
     double whole_cost = 0.0;
