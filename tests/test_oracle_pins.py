@@ -120,6 +120,50 @@ def test_full_layer_vs_pure_python():
     assert np.allclose(Y2, _py_layer(X.tolist(), W.tolist(), None, False)[1], rtol=1e-13, atol=1e-13)
 
 
+def _py_round_bf16(x: float) -> float:
+    """Nearest 8-significant-bit float, ties to even, in plain Python: scale the mantissa of frexp to
+    8 bits (exact), round() it (Python rounds exact halves to even), scale back."""
+    if x == 0.0:
+        return 0.0
+    m, e = math.frexp(x)                  # x = m 2^e, 0.5 <= |m| < 1
+    return math.ldexp(round(m * 256.0), e - 8)
+
+
+def test_share_da_vs_pure_python_and_exact_midpoints():
+    """share_da = bf16(G * GeLU'(A)): one rounding, after the multiply, ties to even.  Checked element by
+    element against math.erf / math.exp and a hand-made rounding; the second half feeds products that
+    are exact midpoints between two bf16 numbers (GeLU'(0) = 1/2 exactly, G = twice the midpoint), and
+    values one fp64 ulp on either side of them."""
+    G = RNG.standard_normal((9, 13)) * 3.0
+    A = RNG.standard_normal((9, 13)) * 1.5
+    got = O.share_da(G, A)
+    for i, j in itertools.product(range(9), range(13)):
+        a, g = float(A[i, j]), float(G[i, j])
+        d = 0.5 * (1.0 + math.erf(a / math.sqrt(2.0))) + a * math.exp(-0.5 * a * a) / math.sqrt(2.0 * math.pi)
+        assert got[i, j] == _py_round_bf16(g * d), (i, j)
+        # a slip the kernel could share: rounding G * GeLU' of the ROUNDED derivative, or rounding twice
+        assert abs(got[i, j] - g * d) <= abs(g * d) * 2.0 ** -8
+    # exact midpoints: 1 + (2 n + 1) 2^-8 lies halfway between 1 + n 2^-7 and 1 + (n + 1) 2^-7
+    mids = np.array([(1.0 + (2 * n + 1) * 2.0 ** -8) * s * 2.0 ** ex for n in (0, 1, 2, 63, 126, 127)
+                     for s in (1.0, -1.0) for ex in (-3, 0, 5)])
+    zeros = np.zeros_like(mids)
+    r = O.share_da(2.0 * mids, zeros)
+    for x, y in zip(mids.tolist(), r.tolist()):
+        lo = math.ldexp(math.floor(math.frexp(abs(x))[0] * 256.0), math.frexp(abs(x))[1] - 8)
+        hi = lo + math.ldexp(1.0, math.frexp(abs(x))[1] - 8)
+        even = lo if (int(math.frexp(lo)[0] * 256.0) % 2 == 0) else hi
+        assert abs(y) == even and math.copysign(1.0, y) == math.copysign(1.0, x), (x, y, lo, hi)
+    up = O.share_da(2.0 * np.nextafter(mids, np.inf * np.sign(mids)), zeros)       # just past the midpoint: away from zero
+    dn = O.share_da(2.0 * np.nextafter(mids, 0.0), zeros)                          # just short of it: towards zero
+    for x, u, d_ in zip(mids.tolist(), up.tolist(), dn.tolist()):
+        m, e = math.frexp(abs(x))
+        lo = math.ldexp(math.floor(m * 256.0), e - 8)
+        assert abs(u) == lo + math.ldexp(1.0, e - 8) and abs(d_) == lo, (x, u, d_)
+    # the no-op cases: GeLU'(a) -> 1 for large a, -> 0 for very negative a
+    assert O.share_da(np.array([[3.0]]), np.array([[40.0]]))[0, 0] == 3.0
+    assert O.share_da(np.array([[3.0]]), np.array([[-40.0]]))[0, 0] == 0.0
+
+
 def test_backward_by_finite_differences():
     X, W, b, G = _tiny(4, 5, 6)
     A, _ = O.layer_fwd(X, W, b)
