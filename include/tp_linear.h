@@ -283,13 +283,22 @@ int tp_dgelu(const void* dy, int64_t ld_dy, const void* preact, int64_t ld_pre,
 
 /*
  * tp_bias_grad -- db = 1^T dA: column sums of a bf16 block [rows, cols] (leading dimension ld) into
- * fp32 [cols], in a fixed summation order (the same bits on every call).  This is what tp_linear_bwd
- * writes to db_f32 for the block it forms itself; here for a dA block that already exists (the 1D
- * chain, where dA is the epilogue of the second layer's dX).  HBM-bound.
+ * fp32 [cols], in a summation order fixed by (rows, cols) alone (the same bits on every call).  This is
+ * what tp_linear_bwd writes to db_f32 for the block it forms itself; here for a dA block that already
+ * exists (the 1D chain, where dA is the epilogue of the second layer's dX).  HBM-bound.
+ *   workspace : optional device scratch of >= tp_bias_grad_workspace_size(rows, cols) bytes, 16-byte
+ *               aligned: the rows are then summed in slabs by many workgroups and the slab sums added
+ *               in ascending order by a second kernel.  NULL: one workgroup per 64 columns sums all
+ *               rows (slow when cols is small).  The two forms add in different orders and may differ
+ *               in the last bits; each is reproducible.  Too small or misaligned: TP_ERR_WORKSPACE.
  * Defined by: the bias gradient of the layer of tp_linear_fwd for one column chunk of the bias
- * (Section 2.2 chunking of the output columns).  Errors: TP_ERR_NULL, TP_ERR_SHAPE, TP_ERR_ALIGN, TP_ERR_HIP.
+ * (Section 2.2 chunking of the output columns).
+ * Errors: TP_ERR_NULL, TP_ERR_SHAPE, TP_ERR_ALIGN, TP_ERR_WORKSPACE, TP_ERR_HIP.
  */
-int tp_bias_grad(const void* da, int64_t ld_da, int64_t rows, int64_t cols, void* db_f32, void* hip_stream);
+int tp_bias_grad(const void* da, int64_t ld_da, int64_t rows, int64_t cols, void* db_f32,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+/* Bytes of workspace the slab form of tp_bias_grad wants (0: it would not split the rows).  Host only. */
+size_t tp_bias_grad_workspace_size(int64_t rows, int64_t cols);
 
 /* Human-readable name of a status code (static storage). */
 const char* tp_strerror(int status);

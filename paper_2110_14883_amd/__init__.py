@@ -5,5 +5,5 @@ from .binding import (  # noqa: F401
     EPI_BIAS, EPI_BIAS_GELU, EPI_NONE, MODE_1D_COL, MODE_1D_ROW, MODE_2D, MODE_2P5D, MODE_3D, MODE_3D_GATHERED,
     PASS_DW, PASS_DW_PARTIALS, PASS_DX, PASS_DX_PARTIALS, PASS_FWD, Grid, TpError, lib, tp_block_map, tp_dgelu, tp_linear_bwd,
     tp_linear_fwd, tp_linear_workspace_size, tp_bias_act, tp_linear_bwd_partials, tp_partials_map, tp_bias_grad, plan_opts, tp_strerror,
-    tp_linear_fwd_static, tp_static_scratch_bytes,
+    tp_linear_fwd_static, tp_static_scratch_bytes, tp_bias_grad_workspace_size,
 )

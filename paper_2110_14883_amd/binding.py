@@ -133,7 +133,9 @@ def lib() -> C.CDLL:
         L.tp_dgelu.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                C.c_int64, C.c_int64, C.c_void_p]
         L.tp_bias_grad.restype = C.c_int
-        L.tp_bias_grad.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]
+        L.tp_bias_grad.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.tp_bias_grad_workspace_size.restype = C.c_size_t
+        L.tp_bias_grad_workspace_size.argtypes = [C.c_int64, C.c_int64]
         L.tp_strerror.restype = C.c_char_p
         L.tp_strerror.argtypes = [C.c_int]
         _lib = L
@@ -143,7 +145,7 @@ def lib() -> C.CDLL:
 EXPORTS = ("tp_block_map", "tp_linear_workspace_size", "tp_linear_workspace_size_ex", "tp_linear_fwd", "tp_linear_fwd_ex",
            "tp_linear_bwd", "tp_linear_bwd_ex", "tp_dgelu", "tp_partials_map", "tp_linear_bwd_partials",
            "tp_linear_bwd_partials_ex", "tp_bias_act", "tp_bias_grad", "tp_strerror", "tp_linear_fwd_static",
-           "tp_static_scratch_bytes")
+           "tp_static_scratch_bytes", "tp_bias_grad_workspace_size")
 
 
 # ----------------------------------------------------------------------------- marshalling helpers
@@ -344,8 +346,13 @@ def tp_bias_act(c, bias, epi: int, y, preact=None, rows: int | None = None, cols
     _check(st, "tp_bias_act")
 
 
-def tp_bias_grad(da, db, rows: int | None = None, cols: int | None = None, stream=None) -> None:
+def tp_bias_grad(da, db, rows: int | None = None, cols: int | None = None, workspace=None, stream=None) -> None:
     if rows is None:
         rows, cols = int(da.shape[0]), int(da.shape[1])
     a = _cblk(da)
-    _check(lib().tp_bias_grad(a.ptr, a.ld, int(rows), int(cols), _ptr(db), _stream(stream)), "tp_bias_grad")
+    ws, wsb = _ws(workspace)
+    _check(lib().tp_bias_grad(a.ptr, a.ld, int(rows), int(cols), _ptr(db), ws, wsb, _stream(stream)), "tp_bias_grad")
+
+
+def tp_bias_grad_workspace_size(rows: int, cols: int) -> int:
+    return int(lib().tp_bias_grad_workspace_size(int(rows), int(cols)))

@@ -471,6 +471,9 @@ size_t tp_linear_workspace_size_ex(const tp_grid_t* grid, const tp_dims_t* dims,
     size_t worst = 0;                   // any prefix 1 .. n_steps of the steps may be asked for
     for (int steps = 1; steps <= s.n_steps; ++steps)
         worst = std::max(worst, ws_bytes_for(make_plan(o, s.m, s.n, s.k, steps), s.m, s.n));
+    Share sf;                           // the bias gradient of tp_linear_bwd sums the forward block's columns in two passes
+    if (pass != TP_PASS_FWD && build_share(grid, dims, TP_PASS_FWD, &sf) == TP_OK)
+        worst = std::max(worst, colsum_ws_bytes(sf.m, sf.n));
     return worst;
 }
 
@@ -587,7 +590,10 @@ int tp_linear_bwd_ex(const tp_grid_t* grid, const tp_dims_t* dims, int n_steps_d
     if (want_da) {
         if (launch_dgelu(dy_own->ptr, dy_own->ld, preact_own->ptr, preact_own->ld, da_own_out.ptr, da_own_out.ld,
                          sf.m, sf.n, stream) != hipSuccess) return TP_ERR_HIP;
-        if (db_f32 && launch_colsum(da_own_out.ptr, da_own_out.ld, sf.m, sf.n, static_cast<float*>(db_f32), stream) != hipSuccess)
+        // (two passes over row slabs when the workspace holds the slab sums, else one workgroup per 64 columns)
+        float* const cws = (workspace && aligned16(workspace) && workspace_bytes >= colsum_ws_bytes(sf.m, sf.n))
+                               ? static_cast<float*>(workspace) : nullptr;
+        if (db_f32 && launch_colsum(da_own_out.ptr, da_own_out.ld, sf.m, sf.n, static_cast<float*>(db_f32), cws, stream) != hipSuccess)
             return TP_ERR_HIP;
     }
     if (px.active) if (int e = run_product(o, px, workspace, stream)) return e;
@@ -730,13 +736,20 @@ int tp_dgelu(const void* dy, int64_t ld_dy, const void* preact, int64_t ld_pre, 
     return TP_OK;
 }
 
-int tp_bias_grad(const void* da, int64_t ld_da, int64_t rows, int64_t cols, void* db_f32, void* hip_stream) {
+size_t tp_bias_grad_workspace_size(int64_t rows, int64_t cols) {
+    return rows > 0 && cols > 0 ? colsum_ws_bytes(rows, cols) : 0;
+}
+
+int tp_bias_grad(const void* da, int64_t ld_da, int64_t rows, int64_t cols, void* db_f32, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
     if (!da || !db_f32) return TP_ERR_NULL;
     if (rows < 0 || cols < 0) return TP_ERR_SHAPE;
     if (!aligned16(da) || !aligned16(db_f32) || (cols & 7) || (ld_da & 7)) return TP_ERR_ALIGN;
     if (ld_da < cols) return TP_ERR_SHAPE;
+    if (workspace && (!aligned16(workspace) || workspace_bytes < colsum_ws_bytes(rows, cols))) return TP_ERR_WORKSPACE;
     if (cols == 0) return TP_OK;
-    if (launch_colsum(da, ld_da, rows, cols, static_cast<float*>(db_f32), static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    if (launch_colsum(da, ld_da, rows, cols, static_cast<float*>(db_f32), static_cast<float*>(workspace),
+                      static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return TP_ERR_HIP;
     return TP_OK;
 }

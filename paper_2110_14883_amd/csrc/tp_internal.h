@@ -64,7 +64,8 @@ hipError_t launch_gemm4(int form, const GemmArgs& args, hipStream_t stream);   /
 hipError_t launch_reduce(const ReduceArgs& args, hipStream_t stream);
 hipError_t launch_dgelu(const void* dy, int64_t ld_dy, const void* pre, int64_t ld_pre,
                         void* da, int64_t ld_da, int64_t rows, int64_t cols, hipStream_t stream);
-hipError_t launch_colsum(const void* da, int64_t ld, int64_t rows, int64_t cols, float* out, hipStream_t stream);
+hipError_t launch_colsum(const void* da, int64_t ld, int64_t rows, int64_t cols, float* out, float* ws, hipStream_t stream);
+size_t colsum_ws_bytes(int64_t rows, int64_t cols);     // 0: the column sum needs no workspace
 // y = [GeLU](c + bias) over an fp32 [rows][cols] block, optional bf16 copy of c + bias
 hipError_t launch_bias_act(const float* c, int64_t ldc, const void* bias, int gelu, void* y, int64_t ldy, int y_f32,
                            void* pre, int64_t ldp, int64_t rows, int64_t cols, hipStream_t stream);

@@ -162,7 +162,7 @@ def run_share(grid, dims, n_steps=None, y_dtype="bf16", dx_dtype="bf16", backwar
     T.tp_linear_bwd(grid, dims, sx, sw, da_row_blocks=da_row_d, w_blocks_dx=w_dx_d, x_blocks_dw=x_dw_d,
                     da_col_blocks=da_col_d, dx=dx, dw=dw, workspace=ws)
     if want_db:
-        T.tp_bias_grad(da_row_d[own_x] if own_x >= 0 else da_col_d[own_w], db)
+        T.tp_bias_grad(da_row_d[own_x] if own_x >= 0 else da_col_d[own_w], db, workspace=ws)
     torch.cuda.synchronize()
     check(host64(dx[sel]), dX, dx_dtype, "dX")
     check(host64(dw[wsel]), dW, "f32", "dW")
@@ -190,7 +190,7 @@ def run_share(grid, dims, n_steps=None, y_dtype="bf16", dx_dtype="bf16", backwar
                     w_blocks_dx=w_dx_d, x_blocks_dw=x_dw_d,
                     da_col_blocks=[da_out if i == own_w else da_col_d[i] for i in range(sw)], dx=dx2, dw=dw2, workspace=ws)
     if want_db:
-        T.tp_bias_grad(da_out, db2)
+        T.tp_bias_grad(da_out, db2, workspace=ws)       # (the same workspace: the same slab sums, the same order)
     torch.cuda.synchronize()
     assert torch.equal(dx1, dx2), "dX: own-slot path differs from the ready-made path on the same dA block"
     assert torch.equal(dw1, dw2), "dW: own-slot path differs from the ready-made path on the same dA block"

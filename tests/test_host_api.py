@@ -219,6 +219,11 @@ def test_argument_errors_before_any_launch():
     assert _st(lambda: T.tp_bias_grad((0x10000, 64), 0, 4, 64, stream=0)) == 1
     assert _st(lambda: T.tp_bias_grad((0x10000, 64), 0x20000, 4, 60, stream=0)) == 5
     assert _st(lambda: T.tp_bias_grad((0x10000, 56), 0x20000, 4, 64, stream=0)) == 4
+    # slab form: the workspace must hold the slab sums
+    need = T.tp_bias_grad_workspace_size(32896, 2560)
+    assert need > 0 and need % (2560 * 4) == 0 and T.tp_bias_grad_workspace_size(100, 64) == 0
+    assert _st(lambda: T.tp_bias_grad((0x10000, 2560), 0x20000, 32896, 2560, workspace=(0x30000, need - 4), stream=0)) == 7
+    assert _st(lambda: T.tp_bias_grad((0x10000, 2560), 0x20000, 32896, 2560, workspace=(0x30008, need), stream=0)) == 7
     # plan options are validated like any other argument
     for bad in (dict(tile=6), dict(split_k=9), dict(group_m=65), dict(rotate=3), dict(trim=-1)):
         with T.plan_opts(**bad):
