@@ -203,6 +203,38 @@ def chunk(T: np.ndarray, nr: int, nc: int, r: int, c: int) -> np.ndarray:
     return T[r * h:(r + 1) * h, c * w:(c + 1) * w]
 
 
+def stored_elements(g: Grid, M: int, h: int) -> dict:
+    """What one rank keeps of a model of two h x h linear layers on M tokens (the paper's range test,
+    Section 4, Memory Efficiency), counted from the chunking rules of Section 2.2: every tensor the
+    scheme partitions is stored as one chunk, a tensor it replicates is stored whole.  Returns the
+    element counts {"narrow": ..., "wide": ...}: narrow = inputs, weights, biases, activations and
+    activation gradients, wide = weight gradients and the partial sums a scheme leaves unreduced
+    (the caller prices them, e.g. 2 and 4 bytes)."""
+    check_grid(g, M, h, h)
+    rc, kc, cc = chunk_counts(g)
+    if g.mode in (MODE_1D_COL, MODE_1D_ROW):
+        n = g.p
+        # the first weight is cut by columns, the second by rows; what lies between them is cut by
+        # columns, everything at the layer pair's two ends is whole (and the ends' results are partial sums)
+        whole, cut = M * h, M * h // n
+        narrow = whole            # X
+        narrow += 3 * cut         # saved pre-activation, activation, its gradient
+        narrow += whole           # upstream gradient of the pair's output
+        narrow += 2 * (h * h // n) + h // n + h          # W1[:, r], W2[r, :], b1[r], b2
+        wide = 2 * whole          # Y and dX, each a partial sum over the ranks
+        wide += 2 * (h * h // n)  # the two weight gradients
+        return {"narrow": narrow, "wide": wide}
+    act = (M // rc) * (h // cc)   # every [M, h] tensor is stored as one chunk of the activation grid
+    if g.mode == MODE_3D:
+        w = (h // (g.p * g.p)) * (h // g.p)              # both matrices of a product are stored as [P/p^2, Q/p]
+    else:
+        w = (h // kc) * (h // cc)                        # 2D / 2.5D: one chunk of the q x q weight grid (on every depth layer)
+    narrow = 7 * act              # X, A1, Z, Y, dY, dA1, dX
+    narrow += 2 * w + 2 * (h // cc)                      # two weights, two bias chunks
+    wide = 2 * w                  # two weight gradients
+    return {"narrow": narrow, "wide": wide}
+
+
 # ----------------------------------------------------------------------------- one rank's share from its blocks
 def share_fwd(x_blocks, w_blocks, bias=None, act=True, rows=None):
     """C = sum_k X_k W_k (k upward), A = C + b, Y = GeLU(A).  Returns (A, Y); ``rows`` restricts

@@ -79,7 +79,8 @@ def _rand(gen, rows, cols, std=1.0):
 
 
 def build_share(grid: B.Grid, M: int, h: int, gen):
-    """Device buffers and the list of library calls of one rank's two-layer step.  Returns (calls, flops)."""
+    """Device buffers and the list of library calls of one rank's two-layer step.  Returns (calls, flops,
+    bufs): bufs names every input block and every output of the step (what a parity check needs)."""
     import torch
     f32, bf = torch.float32, torch.bfloat16
     empty = lambda r, c, dt=bf: torch.empty((r, c), dtype=dt, device="cuda")
@@ -102,7 +103,8 @@ def build_share(grid: B.Grid, M: int, h: int, gen):
             lambda: B.tp_linear_bwd(g1, dims, 1, 1, da_row_blocks=[dA1], w_blocks_dx=[W1], x_blocks_dw=[X],
                                     da_col_blocks=[dA1], dx=dX, dw=dW1, workspace=ws),
         ]
-        return calls, 6 * 2.0 * M * h * hb
+        bufs = dict(X=X, W1=W1, b1=b1, W2=W2, G=G, Z=Z, A1=A1, Y=Y, dA1=dA1, dW2=dW2, dX=dX, dW1=dW1)
+        return calls, 6 * 2.0 * M * h * hb, bufs
     fm = B.tp_block_map(grid, dims, B.PASS_FWD)
     xm = B.tp_block_map(grid, dims, B.PASS_DX)
     wm = B.tp_block_map(grid, dims, B.PASS_DW)
@@ -139,7 +141,11 @@ def build_share(grid: B.Grid, M: int, h: int, gen):
         lambda: B.tp_linear_bwd(grid, dims, S, S, da_row_blocks=da_row, w_blocks_dx=w1x, x_blocks_dw=x_col,
                                 da_col_blocks=da_col, dx=dX, dw=dW1, workspace=ws),
     ]
-    return calls, 6 * 2.0 * m * n * k * S
+    bufs = dict(steps=S, own_fwd=[fm["a"][s] == own for s in range(S)], own_dx=[xm["a"][s] == own for s in range(S)],
+                own_dw=[wm["b"][s] == own for s in range(S)],
+                x1=x1, w1=w1, b1=b1, b2=b2, z2=z2, w2=w2, g_row=g_row, w2x=w2x, z_col=z_col, g_col=g_col,
+                da_row=da_row, w1x=w1x, x_col=x_col, da_col=da_col, Z=Z, A1=A1, Y=Y, dA1=dA1, dW2=dW2, dX=dX, dW1=dW1)
+    return calls, 6 * 2.0 * m * n * k * S, bufs
 
 
 def run_point(name: str, grid: B.Grid, batch: int, h: int, iters: int) -> dict:
@@ -150,7 +156,7 @@ def run_point(name: str, grid: B.Grid, batch: int, h: int, iters: int) -> dict:
     base = torch.cuda.memory_allocated()
     gen = torch.Generator(device="cuda")
     gen.manual_seed(211014883 + 131 * batch + h)
-    calls, flops = build_share(grid, M, h, gen)
+    calls, flops, _ = build_share(grid, M, h, gen)
     torch.cuda.synchronize()
     resident = torch.cuda.memory_allocated() - base           # live buffers of the step (set-up temporaries are gone)
     import time

@@ -571,6 +571,49 @@ def test_bias_grad_slab_form_and_single_pass():
             assert torch.equal(outs[-1], outs[-2]), "bias gradient is not reproducible"
 
 
+# ----------------------------------------------------------------------------- the two-layer chain of the range test
+@pytest.mark.parametrize("name,grid,M,h", [
+    ("1d_p4", T.Grid(T.MODE_1D_COL, p=4, ri=1), 520, 4 * 136),
+    ("2d_q2", T.Grid(T.MODE_2D, q=2, ri=1, rj=0), 2 * 300, 2 * 264),
+    ("2p5d_q2_d2", T.Grid(T.MODE_2P5D, q=2, d=2, ri=1, rj=0, rk=1), 4 * 150, 2 * 264),
+    ("3d_p2", T.Grid(T.MODE_3D, p=2, ri=1, rj=0, rk=1), 4 * 130, 2 * 328),
+], ids=["1d_p4", "2d_q2", "2p5d_q2_d2", "3d_p2"])
+def test_range_test_two_layer_chain(name, grid, M, h):
+    """The call chain of the range test (two linear layers, forward and backward, the rank's own
+    intermediate blocks handed from call to call) at one small point per scheme: every output against
+    the oracle run on the bits the producing call was given."""
+    from paper_2110_14883_amd import range_test as R
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(14883 + M + h)
+    calls, _, b = R.build_share(grid, M, h, gen)
+    for fn in calls:
+        fn()
+    torch.cuda.synchronize()
+    h64 = host64
+    if grid.mode == T.MODE_1D_COL:
+        A, Z = O.share_fwd([h64(b["X"])], [h64(b["W1"])], h64(b["b1"]))
+        check(h64(b["A1"]), A, "bf16", f"{name}: A1 saved"); check(h64(b["Z"]), Z, "bf16", f"{name}: Z")
+        _, Y = O.share_fwd([h64(b["Z"])], [h64(b["W2"])], None, act=False)
+        check(h64(b["Y"]), Y, "f32", f"{name}: Y partial")
+        dA1 = O.round_to_bf16(O.share_dx([h64(b["G"])], [h64(b["W2"])]) * O.dgelu(h64(b["A1"])))
+        check(h64(b["dA1"]), dA1, "bf16", f"{name}: dA1")
+        check(h64(b["dW2"]), O.share_dw([h64(b["Z"])], [h64(b["G"])]), "f32", f"{name}: dW2")
+        check(h64(b["dX"]), O.share_dx([h64(b["dA1"])], [h64(b["W1"])]), "f32", f"{name}: dX partial")
+        check(h64(b["dW1"]), O.share_dw([h64(b["X"])], [h64(b["dA1"])]), "f32", f"{name}: dW1")
+        return
+    L = lambda key: [h64(t) for t in b[key]]
+    A, Z = O.share_fwd(L("x1"), L("w1"), h64(b["b1"]))
+    check(h64(b["A1"]), A, "bf16", f"{name}: A1 saved"); check(h64(b["Z"]), Z, "bf16", f"{name}: Z")
+    assert any(b["own_fwd"]) == any(t is b["Z"] for t in b["z2"])
+    _, Y = O.share_fwd(L("z2"), L("w2"), h64(b["b2"]), act=False)          # (z2 holds the GPU's own Z block where the map says so)
+    check(h64(b["Y"]), Y, "bf16", f"{name}: Y")
+    dA1 = O.round_to_bf16(O.share_dx(L("g_row"), L("w2x")) * O.dgelu(h64(b["A1"])))
+    check(h64(b["dA1"]), dA1, "bf16", f"{name}: dA1")
+    check(h64(b["dW2"]), O.share_dw(L("z_col"), L("g_col")), "f32", f"{name}: dW2")
+    check(h64(b["dX"]), O.share_dx(L("da_row"), L("w1x")), "bf16", f"{name}: dX")
+    check(h64(b["dW1"]), O.share_dw(L("x_col"), L("da_col")), "f32", f"{name}: dW1")
+
+
 # ----------------------------------------------------------------------------- the benchmark shares at full size
 def test_config1_full():
     c = WL.config("c1_2d_q2_fwd")
