@@ -87,7 +87,8 @@ typedef struct { void* ptr; int64_t ld; int dtype; } tp_oblk_t;
  *            3 = 256x128, 4 = 128x128 (eight-wave kernel); 5 = 256x256 on the eight-wave kernel.
  *   split_k: workgroups sharing one C tile along K.  0 automatic, 1..8.
  *   group_m: height, in tile rows, of the groups of the tile order.  0 automatic, 1..64.
- *   rotate : rotate the K-tile order inside a step from C tile to C tile.  0 automatic (on), 1 on, 2 off.
+ *   rotate : rotate the K-tile order inside a step from C tile to C tile.  0 automatic (on for the
+ *            eight-wave kernel, off for the four-wave one), 1 on, 2 off.
  *   trim   : when the tiles are a little more than a whole number of rounds of the persistent
  *            workgroups, run the last tile rows as a second, smaller launch.  0 automatic (on), 1 on, 2 off. */
 typedef struct { int tile, split_k, group_m, rotate, trim; } tp_plan_opts_t;

@@ -16,9 +16,11 @@ constexpr int kCUs = 256;                       // MI355X compute units (8 XCDs 
 constexpr int64_t kMaxLd = (int64_t)1 << 21;    // keeps every in-tile byte offset below 2^31
 
 // Launch-plan options of one call, resolved from the caller's tp_plan_opts_t (NULL = automatic).
+// rotate: -1 automatic (on for the eight-wave kernel, off for the four-wave stream kernel: its workgroups
+// of one XCD share operand panels through the L2 only while they walk K in step), 0 off, 1 on.
 struct Opts { int tile, split, group, rotate, trim; bool eight_wave; };
 int resolve_opts(const tp_plan_opts_t* o, Opts* r) {
-    *r = Opts{0, 0, 0, 1, 1, false};
+    *r = Opts{0, 0, 0, -1, 1, false};
     if (!o) return TP_OK;
     if (o->tile < 0 || o->tile > 5 || o->split_k < 0 || o->split_k > 8 || o->group_m < 0 || o->group_m > 64 ||
         o->rotate < 0 || o->rotate > 2 || o->trim < 0 || o->trim > 2)
@@ -26,7 +28,7 @@ int resolve_opts(const tp_plan_opts_t* o, Opts* r) {
     r->tile = o->tile == 5 ? (int)TILE_256x256 : o->tile;
     r->eight_wave = o->tile == 5;
     r->split = o->split_k; r->group = o->group_m;
-    r->rotate = o->rotate != 2; r->trim = o->trim != 2;
+    r->rotate = o->rotate == 0 ? -1 : (o->rotate == 1); r->trim = o->trim != 2;
     return TP_OK;
 }
 
@@ -297,7 +299,9 @@ bool w4_eligible(int form, const GemmArgs& a) {
 int run_one(const Opts& o, int form, int tile_id, int split_k, const GemmArgs& a, hipStream_t stream) {
     // 256 x 256 tiles run on the four-wave stream kernel unless the eight-wave one is asked for
     if (tile_id == TILE_256x256 && !o.eight_wave && w4_eligible(form, a)) tile_id = TILE_256x256_W4;
-    if (launch_gemm(form, tile_id, a, stream) != hipSuccess) return TP_ERR_HIP;
+    GemmArgs la = a;
+    la.rotate = o.rotate < 0 ? (tile_id != TILE_256x256_W4) : o.rotate;
+    if (launch_gemm(form, tile_id, la, stream) != hipSuccess) return TP_ERR_HIP;
     if (split_k > 1) {
         const int groups = a.n_groups > 1 ? a.n_groups : 1;
         const int64_t mn = (int64_t)a.M * a.N;
@@ -340,7 +344,7 @@ void fill_common(const Opts& o, GemmArgs& a, const Plan& p, int64_t m, int64_t n
     a.M = (int32_t)m; a.N = (int32_t)n; a.K = (int32_t)k; a.n_steps = n_steps;
     a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.split_k = p.split_k; a.group_m = p.group_m;
     a.max_workgroups = kCUs;
-    a.rotate = o.rotate;
+    a.rotate = o.rotate;                       // (run_one resolves "automatic" once it knows the kernel)
 }
 
 bool ws_ok(size_t need, const void* workspace, size_t bytes) {

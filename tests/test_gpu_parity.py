@@ -46,12 +46,14 @@ def test_every_tile_shape_and_split(tile, split):
         run_share(grid, dims, y_dtype="f32", dx_dtype="bf16", label=f"tile {tile} split {split}")
 
 
-def test_k_rotation_off_and_other_group_heights():
+def test_k_rotation_and_other_group_heights():
     """The K-tile rotation and the tile-order group only change the order of work, never the result
     beyond fp32 summation order."""
     grid, dims = T.Grid(T.MODE_2D, q=2, ri=1, rj=1), (2 * 520, 2 * 1032, 2 * 776)
-    with overrides(rotate=0):
-        run_share(grid, dims, y_dtype="f32", dx_dtype="f32", label="rotation off")
+    for tile in (1, 2):          # the four-wave kernel (rotation off unless asked for) and the eight-wave one (on unless asked)
+        for rotate in (0, 1):
+            with overrides(tile=tile, rotate=rotate):
+                run_share(grid, dims, y_dtype="f32", dx_dtype="f32", use_own_slot=False, label=f"tile {tile} rotation {'on' if rotate else 'off'}")
     for group in (1, 7):
         with overrides(group=group):
             run_share(grid, dims, backward=False, label=f"group height {group}")
