@@ -34,13 +34,14 @@ PEAK_BF16_TFLOPS = 2500.0          # MI355X dense bf16 MFMA peak (published figu
 NSETS = int(os.environ.get("TPL_BENCH_NSETS", "3"))   # buffer sets rotated through, so nothing is re-served from the 256 MB MALL
 
 # HBM-side bytes per launch (read + written) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# summarised in profiles/gemm_256x256_config2_1d_mlp.md (scaled there by a copy of known size).
+# summarised in profiles/gemm4_config5_3d.md (scaled there by a copy of known size): the three products
+# of the headline workload.  (Its dX is planned with K split in two: the launch is the fp32-partials
+# instantiation, followed by the fix-up kernel's 252 MB.)
 MEASURED_TRAFFIC_BYTES = {
-    "tpl::tp_gemm_kernel<256, 256, true, false, 2, false>": 1169213543,
-    "tpl::tp_gemm_kernel<256, 256, true, false, 0, true>": 1173524065,
-    "tpl::tp_gemm_kernel<256, 256, true, true, 3, false>": 1245971806,
-    "tpl::tp_gemm_kernel<256, 256, true, true, 0, true>": 1193097948,
-    "tpl::tp_gemm_kernel<256, 256, false, false, 0, true>": 892205206,
+    "tpl::tp_gemm4_kernel<true, false, 2, false>": 2235000000,     # forward NN + bias + GeLU: 1832 MB read, 403 MB written
+    "tpl::tp_gemm4_kernel<false, false, 0, true>": 2655000000,     # dW TN: 2051 MB read, 604 MB written
+    "tpl::tp_gemm4_kernel<true, true, 0, false>": 2038000000,      # dX NT (launched as <true, true, 0, true>): 1837 + 201 MB
+    "tpl::tp_gemm4_kernel<true, true, 0, true>": 2038000000,
 }
 
 
@@ -199,7 +200,7 @@ def main() -> int:
                 cols = [o["da"] if i == inp["own_slot_dw"] else b["da_col"][i] for i in range(sw)]
                 calls += [
                     ("dA = dY*GeLU'(A)", 0.0, "tpl::tp_dgelu_kernel", lambda b=b, o=o: T.tp_linear_bwd(
-                        grid, dims, 0, 0, dy_own=b["g"], preact_own=o["pre"], da_own_out=o["da"], workspace=o["ws"])),
+                        grid, dims, 0, 0, dy_own=b["g"], preact_own=o["pre"], da_own_out=o["da"], workspace=o["ws"]), 6.0 * m * n),
                     ("dX NT", one, gemm_symbol("NT", 0, cfg.dx_dtype == "f32"), lambda b=b, o=o, rows=rows: T.tp_linear_bwd(
                         grid, dims, sx, 0, da_row_blocks=rows, w_blocks_dx=b["wdx"], dx=o["dx"], workspace=o["ws"])),
                     ("dW TN", one, gemm_symbol("TN", 0, True), lambda b=b, o=o, cols=cols: T.tp_linear_bwd(
@@ -226,7 +227,7 @@ def main() -> int:
             sets.append([
                 ("fwd NN +bias+GeLU", one, gemm_symbol("NN", 2, False), lambda b=b, o=o: T.tp_linear_fwd(
                     grid, dims, sf, b["x"], b["w"], b["bias"], T.EPI_BIAS_GELU, o["y"], o["pre"], o["ws"])),
-                ("dA = dY*GeLU'(A)", 0.0, "tpl::tp_dgelu_kernel", lambda b=b, o=o: T.tp_dgelu(b["g"], o["pre"], o["da"])),
+                ("dA = dY*GeLU'(A)", 0.0, "tpl::tp_dgelu_kernel", lambda b=b, o=o: T.tp_dgelu(b["g"], o["pre"], o["da"]), 6.0 * m * n),
                 (f"dX partials NT x{q}", one, gemm_symbol("NT", 0, True), lambda b=b, o=o: T.tp_linear_bwd_partials(
                     grid, dims, o["da"], b["wp"], o["dxp"], None, None, o["ws"])),
                 (f"dW partials TN x{q}", one, gemm_symbol("TN", 0, True), lambda b=b, o=o: T.tp_linear_bwd_partials(
@@ -250,7 +251,7 @@ def main() -> int:
                 ("fwd NN fp32 partial", one, gemm_symbol("NN", 0, True), lambda b=b, o=o: T.tp_linear_fwd(
                     grid, dims, 1, [b["x"]], [b["w"]], None, T.EPI_NONE, o["c"], None, o["ws"])),
                 ("bias+GeLU on the rank's chunk", 0.0, "tpl::tp_bias_act_kernel", lambda b=b, o=o: T.tp_bias_act(
-                    o["c"][l * mc:(l + 1) * mc], b["bias"], T.EPI_BIAS_GELU, o["y"], o["pre"])),
+                    o["c"][l * mc:(l + 1) * mc], b["bias"], T.EPI_BIAS_GELU, o["y"], o["pre"]), 8.0 * mc * fb),
                 ("dX NT fp32 partial", one, gemm_symbol("NT", 0, True), lambda b=b, o=o: T.tp_linear_bwd(
                     grid, dims, 1, 0, da_row_blocks=[b["da"]], w_blocks_dx=[b["w"]], dx=o["dx"], workspace=o["ws"])),
                 ("dW TN fp32 partial", one, gemm_symbol("TN", 0, True), lambda b=b, o=o: T.tp_linear_bwd(
@@ -270,12 +271,12 @@ def main() -> int:
             # trace: 249 us, then 376 us, then a slow return to ~255 us for the same launch).  A short workload
             # timed over 20 steps sits inside that dip, so warm up for >= 80 ms and time >= 250 ms.
             for i in range(3):
-                for _, _, _, fn in sets[i % NSETS]:
+                for _, _, _, fn, *_ in sets[i % NSETS]:
                     fn()
             torch.cuda.synchronize()
             t1 = time.perf_counter()
             for i in range(3):
-                for _, _, _, fn in sets[i % NSETS]:
+                for _, _, _, fn, *_ in sets[i % NSETS]:
                     fn()
             torch.cuda.synchronize()
             est_ms = max((time.perf_counter() - t1) * 1e3 / 3, 1e-3)
@@ -283,7 +284,7 @@ def main() -> int:
             steps = max(20, min(4000, int(250.0 / est_ms) + 1))
         log(f"[bench] {cfg.name}: inputs ready in {time.time() - t0:.1f}s; warmup {warmup}, steps {steps}")
         for i in range(warmup):
-            for _, _, _, fn in sets[i % NSETS]:
+            for _, _, _, fn, *_ in sets[i % NSETS]:
                 fn()
         torch.cuda.synchronize()
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(ncall + 1)] for _ in range(steps)]
@@ -292,17 +293,19 @@ def main() -> int:
         for i in range(steps):
             calls = sets[i % NSETS]
             ev[i][0].record(stream)
-            for j, (_, _, _, fn) in enumerate(calls):
+            for j, (_, _, _, fn, *_) in enumerate(calls):
                 fn()
                 ev[i][j + 1].record(stream)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         ms_step = wall * 1e3 / steps
         per_call = []
-        for j, (label, fl, sym, _) in enumerate(sets[0]):
+        for j, (label, fl, sym, _, *rest) in enumerate(sets[0]):
             ms = sum(ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(steps)) / steps
-            per_call.append(dict(call=label, kernel=sym, ms=round(ms, 4), flops=fl,
-                                 tflops=round(fl / ms / 1e9, 1) if fl else None))
+            row = dict(call=label, kernel=sym, ms=round(ms, 4), flops=fl, tflops=round(fl / ms / 1e9, 1) if fl else None)
+            if rest:        # an HBM-bound elementwise call: algorithmic bytes (read + written) and the rate
+                row.update(bytes=rest[0], tb_per_s=round(rest[0] / ms / 1e9, 2))
+            per_call.append(row)
         graph = None
         if ms_step < 0.2:
             # launch-latency-bound step: also time it replayed from a HIP graph (the library only enqueues
@@ -311,12 +314,12 @@ def main() -> int:
             graphs = []
             with torch.cuda.stream(side):
                 for calls in sets:
-                    for _, _, _, fn in calls:
+                    for _, _, _, fn, *_ in calls:
                         fn()
                     side.synchronize()
                     g = torch.cuda.CUDAGraph()
                     with torch.cuda.graph(g, stream=side):
-                        for _, _, _, fn in calls:
+                        for _, _, _, fn, *_ in calls:
                             fn()
                     graphs.append(g)
             torch.cuda.synchronize()

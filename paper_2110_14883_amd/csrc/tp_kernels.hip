@@ -3,7 +3,9 @@
 // 3D schemes, C = sum_k A_k B_k over the steps, then bias + erf-GeLU; and the two backward
 // products).  bf16 operands, fp32 accumulation in MFMA 32x32x16 tiles.
 //
-// One kernel template serves the three memory forms (NN forward, NT dX, TN dW):
+// The eight-wave GEMM of this file serves the 128 x 256, 256 x 128 and 128 x 128 macro-tiles (and 256 x 256
+// on request), the rest of the file the split-K fix-up and the elementwise kernels.  One kernel template
+// serves the three memory forms (NN forward, NT dX, TN dW):
 //   * persistent workgroups (one per CU) of 8 wave64 walk over the BM x BN tiles of C; a tile's
 //     accumulators stay in registers across ALL steps and all K tiles -- no partial C leaves the
 //     chip unless the host asked for a cross-workgroup split of K;
@@ -19,9 +21,11 @@
 //     consecutive k with one ds_read_b128; LDS rows are 128 B with the 16-byte chunk index
 //     XOR-swizzled so that fragment reads and both kinds of writes are free of bank conflicts;
 //   * the MFMA is issued with the operands swapped (C^T = B^T A^T) so that each lane ends up with
-//     4 consecutive columns of one row of C: bias / GeLU / GeLU' run in registers and the stores
-//     are 8- or 16-byte wide; the first K tile of the next C tile is already in flight while the
-//     epilogue runs;
+//     4 consecutive columns of one row of C: bias / GeLU / GeLU' run in registers, and each 32-row
+//     slab then passes through a wave-private LDS patch so that the stores are whole 128-byte row
+//     segments.  (This kernel's pipeline drains at every C tile: the next tile's first fetch is
+//     issued after the epilogue.  The four-wave kernel of tp_gemm4.hip, which takes the 256 x 256
+//     tiles, keeps its K tiles flowing across C tiles.)
 //   * tile ids are spread so that each XCD (own L2) works on a compact patch of tiles.
 #include "tp_device.h"
 
