@@ -123,8 +123,10 @@ int tp_block_map(const tp_grid_t* grid, const tp_dims_t* dims, int pass,
 /* Bytes of device workspace tp_linear_fwd (pass TP_PASS_FWD), tp_linear_bwd (TP_PASS_DX and
  * TP_PASS_DW each; pass the larger, the two products run one after the other) or
  * tp_linear_bwd_partials (TP_PASS_DX_PARTIALS, TP_PASS_DW_PARTIALS) may need for this share:
- * cross-workgroup split-K partials in fp32.  0 on invalid arguments.  Never more than
- * 8 x m x n x 4 bytes per product. */
+ * cross-workgroup split-K partials in fp32 (never more than 8 x m x n x 4 bytes per product), and, for
+ * the two backward passes, the row-slab sums of the bias gradient (at most 64 x n_fwd x 4 bytes; a
+ * smaller workspace makes tp_linear_bwd fall back to the single-pass column sum).  0 on invalid
+ * arguments. */
 size_t tp_linear_workspace_size(const tp_grid_t* grid, const tp_dims_t* dims, int pass);
 /* The same for calls made with plan options (NULL = tp_linear_workspace_size). */
 size_t tp_linear_workspace_size_ex(const tp_grid_t* grid, const tp_dims_t* dims, int pass, const tp_plan_opts_t* opts);
