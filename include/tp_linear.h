@@ -26,8 +26,9 @@
  * of every block and every `ld` must be multiples of 8 elements and every pointer, the workspace
  * included, 16-byte aligned (128-bit loads and stores), else TP_ERR_ALIGN (TP_ERR_WORKSPACE for the
  * workspace).  The library keeps no mutable state between calls apart from per-device caches of kernel
- * attributes and of the device's compute-unit count; every entry point may be called from several
- * threads at once.
+ * attributes, of the device's compute-unit count and of the address of its built-in scratch array;
+ * every entry point may be called from several threads at once (tp_linear_fwd_static: see its own
+ * note on calls that overlap on one GPU).
  */
 #ifndef TP_LINEAR_H
 #define TP_LINEAR_H
